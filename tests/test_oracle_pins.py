@@ -1,0 +1,427 @@
+"""Pins for the CPU oracle: every function is checked against something other than itself --
+the paper's worked example, closed forms, library routines, invariants or brute force on
+tiny inputs.  No GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import freekv_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_T(rng, shape, dtype="bf16", scale=1.0):
+    x = (rng.standard_normal(shape) * scale).astype(np.float32)
+    return W.decode(W.encode(x, dtype), dtype)
+
+
+def _small_oracle(rng, L, n_q=4, n_kv=2, d=128, p=4, budget=16, sink=4, window=4, tau=0.8,
+                  max_ctx=None, dtype="bf16"):
+    max_ctx = max_ctx or (L + 64)
+    o = O.FreeKVOracle(n_q, n_kv, d, p, budget, sink, window, tau, max_ctx)
+    K = _rand_T(rng, (L, n_kv, d), dtype)
+    V = _rand_T(rng, (L, n_kv, d), dtype)
+    o.load_prefix(K, V)
+    return o, K, V
+
+
+# ---------------------------------------------------------------- Sec. 2.1 dense attention
+def test_dense_attention_matches_library_sdpa():
+    rng = np.random.default_rng(1)
+    n_q, n_kv, d, L = 8, 2, 128, 77
+    q = _rand_T(rng, (n_q, d))
+    K = _rand_T(rng, (L, n_kv, d))
+    V = _rand_T(rng, (L, n_kv, d))
+    ref = O.dense_attention(q, K, V)
+    G = n_q // n_kv
+    tq = torch.from_numpy(q).double()[None, :, None, :]                       # [1, n_q, 1, d]
+    tK = torch.from_numpy(K).double().permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    tV = torch.from_numpy(V).double().permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    lib = torch.nn.functional.scaled_dot_product_attention(tq, tK, tV)[0, :, 0, :].numpy()
+    np.testing.assert_allclose(ref, lib, rtol=1e-12, atol=1e-13)
+
+
+def test_dense_attention_single_token_returns_value():
+    rng = np.random.default_rng(2)
+    q = _rand_T(rng, (4, 128))
+    K = _rand_T(rng, (1, 2, 128))
+    V = _rand_T(rng, (1, 2, 128))
+    out = O.dense_attention(q, K, V)
+    for h in range(4):
+        np.testing.assert_array_equal(out[h], V[0, h // 2].astype(np.float64))
+
+
+def test_gqa_head_mapping_uses_h_over_G():
+    # make KV head 1 all-zero values: heads 2,3 (G=2) must output zeros, heads 0,1 must not
+    rng = np.random.default_rng(3)
+    q = _rand_T(rng, (4, 128))
+    K = _rand_T(rng, (9, 2, 128))
+    V = _rand_T(rng, (9, 2, 128))
+    V[:, 1, :] = 0
+    out = O.dense_attention(q, K, V)
+    assert np.all(out[2:] == 0) and np.all(np.abs(out[:2]).sum(axis=1) > 0)
+
+
+# ---------------------------------------------------------------- Sec. 3.2 summaries
+def test_page_summaries_bruteforce_and_incremental():
+    rng = np.random.default_rng(4)
+    p, L = 4, 23
+    o, K, _ = _small_oracle(rng, L, p=p)
+    kmax, kmin = O.page_summaries(K, p)
+    for j in range((L + p - 1) // p):
+        for m in range(2):
+            for c in range(0, 128, 17):
+                vals = [float(K[t, m, c]) for t in range(j * p, min(L, (j + 1) * p))]
+                assert kmax[j, m, c] == max(vals) and kmin[j, m, c] == min(vals)
+    n_page = kmax.shape[0]
+    np.testing.assert_array_equal(o.kmax[:n_page], kmax)   # token-by-token appends == recomputed
+    np.testing.assert_array_equal(o.kmin[:n_page], kmin)
+    o2 = O.FreeKVOracle(4, 2, 128, p, 16, 4, 4, 0.8, L + 64)
+    o2.load_prefix_bulk(K, K)
+    np.testing.assert_array_equal(o2.kmax, o.kmax)
+    np.testing.assert_array_equal(o2.kmin, o.kmin)
+
+
+# ---------------------------------------------------------------- page weights (steps a-c)
+def _ref_sum_order(vals):
+    """The written order, in pure Python on np.float32 scalars: 16 chunks of 8 left-to-right, then adjacent-pair tree."""
+    chunks = []
+    for ci in range(16):
+        s = np.float32(vals[ci * 8])
+        for u in range(1, 8):
+            s = np.float32(s + np.float32(vals[ci * 8 + u]))
+        chunks.append(s)
+    while len(chunks) > 1:
+        chunks = [np.float32(chunks[i] + chunks[i + 1]) for i in range(0, len(chunks), 2)]
+    return chunks[0]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_page_weight_equals_exhaustive_per_token_evaluation(dtype):
+    """P_raw = sum_c max_{t in page} (q_c * k_{t,c}), bit for bit: products are exact and the
+    maximum over a page commutes with the exact product, so summaries lose nothing."""
+    rng = np.random.default_rng(5)
+    p, L, n_q, n_kv = 4, 20, 4, 2
+    K = _rand_T(rng, (L, n_kv, 128), dtype)
+    q = _rand_T(rng, (n_q, 128), dtype)
+    kmax, kmin = O.page_summaries(K, p)
+    P = O.page_weights(q, kmax, kmin)
+    scale = np.float32(1.0 / math.sqrt(128.0))
+    for h in range(n_q):
+        m = h // (n_q // n_kv)
+        for j in range(L // p):
+            terms = []
+            for c in range(128):
+                prods = [np.float32(q[h, c]) * np.float32(K[t, m, c]) for t in range(j * p, (j + 1) * p)]
+                for t in range(j * p, (j + 1) * p):   # exactness of the fp32 product
+                    assert float(q[h, c]) * float(K[t, m, c]) == float(np.float32(q[h, c]) * np.float32(K[t, m, c]))
+                terms.append(max(prods))
+            expect = np.float32(_ref_sum_order(terms) * scale)
+            assert P[h, j].tobytes() == expect.tobytes()
+
+
+def test_page_weight_is_upper_bound_of_token_logits_and_close_to_fp64():
+    rng = np.random.default_rng(6)
+    p, L = 8, 64
+    K = _rand_T(rng, (L, 2, 128))
+    q = _rand_T(rng, (4, 128))
+    kmax, kmin = O.page_summaries(K, p)
+    P = O.page_weights(q, kmax, kmin)
+    for h in range(4):
+        m = h // 2
+        logits = K[:, m, :].astype(np.float64) @ q[h].astype(np.float64) / math.sqrt(128)
+        ub = np.maximum(q[h].astype(np.float64) * kmax[:, m, :], q[h].astype(np.float64) * kmin[:, m, :]).sum(-1) / math.sqrt(128)
+        np.testing.assert_allclose(P[h], ub, rtol=2e-6, atol=1e-5)
+        for j in range(L // p):
+            assert P[h, j] >= logits[j * p:(j + 1) * p].max() - 1e-4
+
+
+def test_summation_order_is_the_written_one():
+    # values on which chunked-sequential + adjacent tree differs from plain left-to-right and from
+    # a strided (xor 8,4,2,1) tree, so a transposed or re-ordered reduction fails here
+    vals = np.zeros(128, dtype=np.float32)
+    vals[0] = 2.0 ** 24
+    vals[1:8] = 1.0          # inside chunk 0, each +1 is absorbed: chunk 0 stays 2^24
+    vals[8:16] = 1.0         # chunk 1 = 8, combined with chunk 0 first -> 2^24 + 8
+    vals[64] = -(2.0 ** 24)  # chunk 8
+    got = O._canonical_sum128(vals[None, :])[0]
+    assert got == _ref_sum_order(vals) == np.float32(8.0)
+    assert np.float32(np.sum(vals.astype(np.float64))) == np.float32(15.0)   # the exact sum differs
+
+
+# ---------------------------------------------------------------- exp, softmax, pooling (steps d-g)
+def test_exp_spec_close_to_libm_and_exact_at_zero():
+    x = np.linspace(-40.0, 0.0, 20001).astype(np.float32)
+    e = O.exp_spec(x).astype(np.float64)
+    ref = np.exp(x.astype(np.float64))
+    rel = np.abs(e - ref) / ref
+    # the fp32 product x*log2(e) carries up to half an ulp of |t| <= 58: 1.9e-6 absolute in t,
+    # i.e. 1.3e-6 relative in 2^t; the polynomial and the Horner roundings add < 4e-7
+    assert rel.max() < 2.5e-6
+    assert rel[x >= -1.0].max() < 4e-7
+    assert O.exp_spec(np.float32(0.0)) == np.float32(1.0)
+    assert O.exp_spec(np.float32(-60.0)) == 0.0            # below the cut-off t < -64
+    assert np.all(np.diff(O.exp_spec(np.linspace(-30, 0, 4001).astype(np.float32))) >= 0)
+
+
+def test_pooled_scores_sum_to_one_and_match_fp64_softmax_mean():
+    rng = np.random.default_rng(7)
+    G, n_kv, n = 4, 3, 301
+    P = (rng.standard_normal((G * n_kv, n)) * 3).astype(np.float32)
+    s = O.pooled_scores(P, G)
+    assert s.dtype == np.float32 and s.shape == (n_kv, n)
+    np.testing.assert_allclose(s.astype(np.float64).sum(axis=1), 1.0, atol=1e-6)
+    P64 = P.astype(np.float64)
+    sm = np.exp(P64 - P64.max(axis=1, keepdims=True))
+    sm /= sm.sum(axis=1, keepdims=True)
+    ref = sm.reshape(n_kv, G, n).mean(axis=1)
+    np.testing.assert_allclose(s, ref, rtol=2e-6, atol=1e-9)
+
+
+def test_pooling_group_of_one_keeps_the_ranking_of_the_weights():
+    rng = np.random.default_rng(8)
+    P = (rng.standard_normal((2, 200)) * 2).astype(np.float32)
+    s = O.pooled_scores(P, 1)
+    for m in range(2):
+        np.testing.assert_array_equal(np.argsort(-P[m], kind="stable")[:20], np.argsort(-s[m].astype(np.float64), kind="stable")[:20])
+
+
+def test_pooling_is_mean_of_softmax_not_softmax_of_mean():
+    # two heads with opposite preferences: mean of softmaxes puts mass on both pages,
+    # softmax of the mean weight would be flat; also checks the 1/G factor
+    P = np.array([[10.0, 0.0, 0.0], [0.0, 0.0, 10.0]], dtype=np.float32)
+    s = O.pooled_scores(P, 2)[0]
+    assert abs(s[0] - s[2]) < 1e-7 and s[0] > 0.49 and s[1] < 1e-4
+
+
+# ---------------------------------------------------------------- top-k (step h)
+def _bruteforce_topk(score, k):
+    items = [(float(score[i]), i) for i in range(len(score))]
+    chosen = []
+    for _ in range(min(k, len(items))):
+        best = None
+        for s, i in items:
+            if i in chosen:
+                continue
+            if best is None or s > best[0] or (s == best[0] and i < best[1]):
+                best = (s, i)
+        chosen.append(best[1])
+    return sorted(chosen)
+
+
+def test_topk_bruteforce_ties_prefix_and_permutation():
+    rng = np.random.default_rng(9)
+    for trial in range(20):
+        n = int(rng.integers(1, 40))
+        score = rng.integers(0, 6, size=n).astype(np.float32) / 8      # many ties
+        for k in (0, 1, 3, n, n + 2):
+            np.testing.assert_array_equal(O.topk_pages(score, k), _bruteforce_topk(score, k))
+    score = rng.random(50).astype(np.float32)
+    prev = set()
+    for k in range(1, 50):
+        cur = set(O.topk_pages(score, k).tolist())
+        assert prev < cur
+        prev = cur
+    perm = rng.permutation(50)
+    top = set(O.topk_pages(score, 7).tolist())
+    top_perm = set(perm[O.topk_pages(score[perm], 7)].tolist())
+    assert top == top_perm
+    np.testing.assert_array_equal(O.topk_pages(np.array([1, 1, 1, 1], dtype=np.float32), 2), [0, 1])
+
+
+# ---------------------------------------------------------------- Sec. 3.1 / 3.3 correction
+def test_correction_worked_example_from_the_paper():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "correction_example.txt")) if l.strip() and not l.startswith("#")]
+    assert rows
+    for pooled, tau, flagged in rows:
+        G = 4
+        C = np.full(G, float(pooled))
+        assert O.correction_flags(C, G, float(tau))[0] == int(flagged)
+    # mean pooling, not max or min: (0.95 + 0.6)/2 = 0.775 < 0.8, while max would pass
+    assert O.correction_flags(np.array([0.95, 0.6]), 2, 0.8)[0] == 1
+    assert O.correction_flags(np.array([0.95, 0.7]), 2, 0.8)[0] == 0
+    # flags are per KV head
+    np.testing.assert_array_equal(O.correction_flags(np.array([0.9, 0.9, 0.1, 0.1]), 2, 0.8), [0, 1])
+
+
+def test_query_cosine_closed_forms():
+    rng = np.random.default_rng(10)
+    q = _rand_T(rng, (4, 128))
+    np.testing.assert_allclose(O.query_cosine(q * np.float32(2.0), q), 1.0, atol=1e-14)
+    np.testing.assert_allclose(O.query_cosine(-q, q), -1.0, atol=1e-14)
+    a = np.zeros((1, 128), dtype=np.float32); a[0, 0] = 1
+    b = np.zeros((1, 128), dtype=np.float32); b[0, 1] = 1
+    assert O.query_cosine(a, b)[0] == 0.0
+    c = np.zeros((1, 128), dtype=np.float32); c[0, 0] = 3; c[0, 1] = 4
+    np.testing.assert_allclose(O.query_cosine(a, c)[0], 0.6, atol=1e-15)
+    assert O.query_cosine(np.zeros((1, 128), np.float32), a)[0] == 0.0
+    ref = np.array([np.dot(q[h].astype(np.float64), q[(h + 1) % 4]) / np.linalg.norm(q[h].astype(np.float64)) / np.linalg.norm(q[(h + 1) % 4].astype(np.float64)) for h in range(4)])
+    np.testing.assert_allclose(O.query_cosine(q, np.roll(q, -1, axis=0)), ref, atol=1e-14)
+
+
+# ---------------------------------------------------------------- geometry of the budget (Sec. 2.1)
+def test_geometry_budget_sink_window():
+    p, B, S, Wn = 32, 2048, 512, 512
+    g = O.geometry(32768 + 5, p, B, S, Wn)
+    assert (g.n_full, g.r, g.n_sink, g.n_win, g.cand_lo, g.n_cand, g.k_eff) == (1024, 5, 16, 16, 16, 992, 32)
+    # |I| = B: sink + selected + window tokens, plus the open page's r tokens
+    assert (g.n_sink + g.k_eff + g.n_win) * p == B
+    g = O.geometry(40, p, B, S, Wn)          # shorter than the sink: everything is sink/open page
+    assert (g.n_sink, g.n_win, g.n_cand, g.k_eff) == (1, 0, 0, 0)
+    g = O.geometry(1024 + 31, p, B, S, Wn)   # context = S + W: still nothing to select
+    assert (g.n_sink, g.n_win, g.n_cand) == (16, 16, 0)
+    g = O.geometry(1024 + 32 * 3, p, B, S, Wn)
+    assert (g.n_cand, g.k_eff, g.cand_lo) == (3, 3, 16)
+
+
+def test_attended_tokens_always_hold_sink_window_and_open_page():
+    rng = np.random.default_rng(11)
+    o, K, V = _small_oracle(rng, 61, p=4, budget=24, sink=8, window=8)
+    g = o.geom()
+    ids = np.array([5, 9], dtype=np.int32)
+    tok = o.attended_tokens(ids)
+    expect = list(range(0, 8)) + list(range(20, 24)) + list(range(36, 40)) + list(range(52, 60)) + [60]
+    assert tok.tolist() == expect and len(tok) == 24 + g.r
+
+
+# ---------------------------------------------------------------- whole step
+def test_budget_covering_the_context_equals_dense_attention():
+    rng = np.random.default_rng(12)
+    L, p = 50, 4
+    o, K, V = _small_oracle(rng, L, p=p, budget=64, sink=4, window=8, max_ctx=64)
+    Kall, Vall = K, V
+    for step in range(6):
+        q = _rand_T(rng, (4, 128))
+        k_new = _rand_T(rng, (2, 128))
+        v_new = _rand_T(rng, (2, 128))
+        Kall = np.concatenate([Kall, k_new[None]], 0)
+        Vall = np.concatenate([Vall, v_new[None]], 0)
+        res = o.step(q, k_new, v_new)
+        assert res["geom"].k_eff == res["geom"].n_cand
+        np.testing.assert_allclose(res["out"], O.dense_attention(q, Kall, Vall), rtol=1e-12, atol=1e-13)
+
+
+def _stateless_select_attend(o_args, K, V, q_sel, q_att):
+    o = O.FreeKVOracle(*o_args)
+    o.load_prefix(K, V)
+    ids, _, _ = o.select(q_sel)
+    return o.attend(q_att, ids), ids
+
+
+@pytest.mark.parametrize("tau,mode", [(1.5, "no_speculation"), (-1.0, "no_correction")])
+def test_tau_limits_reduce_to_stateless_selection(tau, mode):
+    """tau > 1: every step selects with its own query (no speculation, App. B.3 table of thresholds);
+    tau <= -1: never corrects, so step i attends with the pages selected by q_{i-1} on the context of step i-1."""
+    rng = np.random.default_rng(13)
+    L, p = 64, 4
+    args = (4, 2, 128, p, 24, 4, 8, tau, 128)
+    o = O.FreeKVOracle(*args)
+    K = _rand_T(rng, (L, 2, 128)); V = _rand_T(rng, (L, 2, 128))
+    o.load_prefix(K, V)
+    Kall, Vall = K, V
+    prev_q = None
+    prev_KV = None
+    for step in range(7):
+        q = _rand_T(rng, (4, 128))
+        k_new = _rand_T(rng, (2, 128)); v_new = _rand_T(rng, (2, 128))
+        Kall = np.concatenate([Kall, k_new[None]], 0); Vall = np.concatenate([Vall, v_new[None]], 0)
+        res = o.step(q, k_new, v_new)
+        if mode == "no_speculation" or step == 0:
+            assert res["flags"].all()
+            ref, ids = _stateless_select_attend(args, Kall, Vall, q, q)
+            np.testing.assert_array_equal(res["used_ids"], ids)
+        else:
+            assert not res["flags"].any()
+            o_prev = O.FreeKVOracle(*args); o_prev.load_prefix(*prev_KV)
+            ids, _, _ = o_prev.select(prev_q)
+            o_now = O.FreeKVOracle(*args); o_now.load_prefix(Kall, Vall)
+            ref = o_now.attend(q, ids)
+            np.testing.assert_array_equal(res["used_ids"], ids)
+        np.testing.assert_allclose(res["out"], ref, rtol=1e-12, atol=1e-13)
+        prev_q, prev_KV = q, (Kall, Vall)
+
+
+def test_attention_does_not_depend_on_the_order_of_selected_pages():
+    rng = np.random.default_rng(14)
+    o, K, V = _small_oracle(rng, 80, p=4, budget=32, sink=4, window=4)
+    q = _rand_T(rng, (4, 128))
+    a = o.attend(q, np.array([[3, 7, 11, 12, -1, -1], [2, 5, 6, 9, -1, -1]], dtype=np.int32))
+    b = o.attend(q, np.array([[12, 3, -1, 11, 7, -1], [9, 6, 5, 2, -1, -1]], dtype=np.int32))
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_selection_is_group_consistent_and_within_candidates():
+    rng = np.random.default_rng(15)
+    o, K, V = _small_oracle(rng, 100, p=4, budget=24, sink=4, window=8)
+    q = _rand_T(rng, (4, 128))
+    ids, P, score = o.select(q)
+    g = o.geom()
+    assert ids.shape == (2, 3) and P.shape == (4, g.n_cand) and score.shape == (2, g.n_cand)
+    for m in range(2):
+        row = ids[m]
+        assert np.all(np.diff(row) > 0) and row.min() >= g.cand_lo and row.max() < g.cand_lo + g.n_cand
+        # brute force: the picked pages are exactly the 3 best scores
+        best = sorted(np.argsort(-score[m].astype(np.float64), kind="stable")[:3] + g.cand_lo)
+        assert row.tolist() == best
+
+
+def test_selection_finds_the_page_holding_a_planted_key():
+    rng = np.random.default_rng(16)
+    o = O.FreeKVOracle(4, 2, 128, 4, 16, 4, 4, 0.8, 256)
+    K = _rand_T(rng, (120, 2, 128), scale=0.1); V = _rand_T(rng, (120, 2, 128))
+    q = _rand_T(rng, (4, 128))
+    K[4 * 17 + 2, 0, :] = q[0] * np.float32(2.0)      # page 17 for KV head 0
+    K[4 * 9 + 1, 1, :] = q[3] * np.float32(2.0)       # page 9 for KV head 1
+    o.load_prefix(K, V)
+    ids, _, _ = o.select(q)
+    assert 17 in ids[0] and 9 in ids[1]
+
+
+def test_recall_bookkeeping_misses():
+    rng = np.random.default_rng(17)
+    o, K, V = _small_oracle(rng, 100, p=4, budget=24, sink=4, window=8, tau=0.8)
+    q = _rand_T(rng, (4, 128))
+    r0 = o.step(q, _rand_T(rng, (2, 128)), _rand_T(rng, (2, 128)))
+    assert [sorted(set(r0["new_ids"][m].tolist()) - {-1}) for m in range(2)] == r0["miss"]     # cold cache
+    r1 = o.step(q, _rand_T(rng, (2, 128), scale=1e-3), _rand_T(rng, (2, 128)))
+    for m in range(2):   # same query, no new full page: same selection, nothing to recall
+        assert r1["new_ids"][m].tolist() == r0["new_ids"][m].tolist() and r1["miss"][m] == []
+    r2 = o.step(-q, _rand_T(rng, (2, 128)), _rand_T(rng, (2, 128)))
+    for m in range(2):
+        assert r2["miss"][m] == sorted(set(r2["new_ids"][m].tolist()) - set(r1["new_ids"][m].tolist()))
+        assert r2["flags"][m] == 1     # cos(-q, q) = -1 < tau
+
+
+# ---------------------------------------------------------------- layout arithmetic (Sec. 4.2) and generator
+def test_transfer_units_from_the_paper():
+    rows = dict(l.split() for l in open(os.path.join(GOLDEN, "transfer_units.txt")) if l.strip() and not l.startswith("#"))
+    d, p, esz = 128, 32, 2
+    assert int(rows["NHD"]) == d * esz and int(rows["HND"]) == p * d * esz and int(rows["HOSTPOOL"]) == 2 * p * d * esz
+
+
+def test_generator_statistics_and_determinism():
+    wl = W.get_workload("c1")
+    q, qb = W.query_stream(wl, 0, 0)
+    a, b = q[1:].astype(np.float64), q[:-1].astype(np.float64)
+    cos = (a * b).sum(-1) / np.sqrt((a * a).sum(-1) * (b * b).sum(-1))
+    assert abs(cos.mean() - wl.rho / math.sqrt(wl.rho ** 2 + wl.q_noise ** 2)) < 0.03   # cf. similarity > 0.84, Sec. 3.1
+    q2, qb2 = W.query_stream(wl, 0, 0)
+    np.testing.assert_array_equal(qb, qb2)
+    (K, Kb), (V, Vb) = W.kv_prefix(wl, 0, 0, n_tokens=256)
+    np.testing.assert_array_equal(W.decode(Kb, wl.dtype), K)
+    ratio = K[..., list(W.OUTLIER_CHANNELS)].std() / K[..., [0, 1, 2, 3]].std()
+    assert 7.0 < ratio < 9.0
+    (K2, _), _ = W.kv_prefix(wl, 1, 0, n_tokens=256)
+    assert not np.array_equal(K, K2)
+    # storage rounding against a library: ties-to-even for bf16 and fp16
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(4096).astype(np.float32) * 3,
+                        np.array([1.00390625, 1.01171875, -3.0e-5, 65504.0, 0.0, -0.0], dtype=np.float32)])
+    for name, tdt in (("bf16", torch.bfloat16), ("fp16", torch.float16)):
+        lib = torch.from_numpy(x).to(tdt).view(torch.int16).numpy().view(np.uint16)
+        np.testing.assert_array_equal(W.encode(x, name), lib)
+        np.testing.assert_array_equal(W.decode(lib, name), torch.from_numpy(x).to(tdt).float().numpy())
