@@ -1,0 +1,179 @@
+/* freekv.h -- C ABI of the MI355X retrieval-decode library.
+ *
+ * One decode step of one layer, as the paper states it:
+ *   - attention of head h over its KV head m = h / G           (Sec. 2.1)
+ *   - a budget of B tokens: S sink + W window tokens always kept, the other
+ *     (B - S - W) / p pages picked per KV head, the same pages for the whole
+ *     query group                                               (Sec. 2.1, 3.2)
+ *   - pages are scored through their min-max key summaries, softmax over
+ *     pages, mean over the group, top-k                         (Sec. 3.2)
+ *   - the step attends with the pages picked at the previous step, unless the
+ *     group-mean cosine similarity of this step's and the previous step's
+ *     queries is below tau, in which case that KV head re-selects first
+ *                                                               (Sec. 3.2, 3.3)
+ *   - with the whole KV cache in host memory, picked pages that are not in the
+ *     GPU page cache are recalled as one contiguous 2*p*d block per
+ *     (page, KV head)                                           (Sec. 4.1, 4.2)
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative FKV_E* code; nothing
+ *     throws or aborts.  fkv_last_error() gives a text for the last failure.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  `stream` arguments are hipStream_t passed as void*
+ *     (NULL = the default stream).  Calls only enqueue work on the stream
+ *     unless stated otherwise.
+ *   - Element type T of q/K/V is cfg.dtype (2 bytes).  Attention output is fp32.
+ *   - One context, one calling thread.  Calls on one context that overlap in
+ *     time on different streams are only safe as fkv_decode_step issues them.
+ *   - The caller owns q/k/v/out buffers, both arenas and the streams; arenas
+ *     must outlive the context.  The library owns what it carves from them.
+ */
+#ifndef FREEKV_H
+#define FREEKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FKV_OK       0
+#define FKV_EINVAL  -1   /* bad configuration or argument                         */
+#define FKV_ESTATE  -2   /* call order (e.g. attention before any selection)      */
+#define FKV_ERANGE  -3   /* layer / page / token count out of range               */
+#define FKV_ENOMEM  -4   /* arena too small                                       */
+#define FKV_EHIP    -5   /* a HIP call failed; see fkv_last_error                 */
+
+#define FKV_DTYPE_FP16 0
+#define FKV_DTYPE_BF16 1
+
+#define FKV_PLACE_HBM  0  /* whole KV cache resident in HBM, pages read in place   */
+#define FKV_PLACE_HOST 1  /* whole KV cache in a pinned host pool; HBM holds sink,
+                             window and a double-buffered cache of picked pages    */
+
+/* which page list sparse attention reads */
+#define FKV_USE_ACTIVE   0  /* pages committed at the previous step (reuse)        */
+#define FKV_USE_PENDING  1  /* pages picked at this step                           */
+#define FKV_USE_BY_FLAG  2  /* per KV head: pending if its correction flag is set  */
+
+/* which KV heads fkv_recall_pages serves */
+#define FKV_HEADS_ALL        0
+#define FKV_HEADS_FLAGGED    1
+#define FKV_HEADS_UNFLAGGED  2
+
+typedef struct fkv_ctx fkv_ctx;
+
+typedef struct {
+  int32_t n_layers;
+  int32_t batch;           /* requests; all share one context length                */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;      /* G = n_q_heads / n_kv_heads, 1 <= G <= 8               */
+  int32_t head_dim;        /* must be 128                                           */
+  int32_t page_size;       /* must be 32                                            */
+  int32_t max_ctx;         /* multiple of page_size                                 */
+  int32_t budget_tokens;   /* B; multiples of page_size, B >= S + W                 */
+  int32_t sink_tokens;     /* S                                                     */
+  int32_t window_tokens;   /* W                                                     */
+  int32_t dtype;           /* FKV_DTYPE_*                                           */
+  int32_t placement;       /* FKV_PLACE_*                                           */
+  float   tau;             /* correction threshold; <= -1 never corrects, > 1 always */
+  int32_t reserved;        /* 0                                                     */
+} fkv_config;
+
+/* Bytes the library needs: a device arena, and (placement HOST) a pinned,
+ * device-mapped host arena for the whole KV pool.  Host pointers in/out. */
+int fkv_arena_bytes(const fkv_config* cfg, size_t* dev_bytes, size_t* host_bytes);
+
+/* Create a context on the current device.  dev_arena: device memory, 256-byte
+ * aligned, >= dev_bytes.  host_arena: pinned host memory reachable from the
+ * device under the same address (hipHostMalloc / torch pin_memory), or NULL
+ * for placement HBM.  Zero-fills the device arena (blocking). */
+int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes,
+               void* host_arena, size_t host_bytes, fkv_ctx** out);
+int fkv_destroy(fkv_ctx* ctx);
+/* Text of the last error of this context (ctx == NULL: of the last failed create). */
+const char* fkv_last_error(const fkv_ctx* ctx);
+/* Tokens currently cached for `layer` (host-side counter), or a negative code. */
+int fkv_context_len(const fkv_ctx* ctx, int32_t layer);
+
+/* ---- data plane ------------------------------------------------------- */
+
+/* Bulk-load a context of n_tokens (replaces the layer's state): stores K/V in
+ * the paged layout, builds the min-max page summaries (Sec. 3.2) and, for
+ * placement HOST, writes every page to the host pool in its contiguous
+ * per-(page, KV head) unit (Sec. 4.2).  K, V: dev, [batch, n_tokens, n_kv, d]. */
+int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* V_dev,
+                    int32_t n_tokens, void* stream);
+
+/* Append one token per request: k_new, v_new dev [batch, n_kv, d].  Folds the key
+ * into the open page's running min/max (Sec. 3.2).  Placement HOST: when the
+ * token fills a page, the page is offloaded to the host pool on copy_stream
+ * (the transpose happens once, when the page is offloaded -- Sec. 4.2). */
+int fkv_kv_append(fkv_ctx* ctx, int32_t layer, const void* k_new_dev, const void* v_new_dev,
+                  void* stream, void* copy_stream);
+
+/* Recompute the summaries of pages [first_page, first_page + n_pages) from the
+ * stored keys (placement HBM only). */
+int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int32_t n_pages,
+                            void* stream);
+
+/* ---- the loop's primitives --------------------------------------------- */
+
+/* Correction test (Sec. 3.1, 3.3): per KV head, 1 iff the group mean of
+ * cos(q, q_prev) is < tau, or there is no previous query.  q dev [batch, n_q, d];
+ * flags_dev (may be NULL) receives [batch, n_kv] bytes.  Also stages q as the
+ * next step's q_prev; it becomes q_prev at fkv_commit. */
+int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flags_dev, void* stream);
+
+/* Sel(q) for every KV head (Sec. 3.2): scores candidate pages, picks the
+ * k = (B-S-W)/p best (ties to the lower page id).  page_ids_dev (may be NULL)
+ * receives [batch, n_kv, k] int32, ascending, padded with -1.  The result is
+ * kept as the PENDING selection; for placement HOST the pages it misses in the
+ * GPU page cache are worked out too. */
+int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* page_ids_dev, void* stream);
+
+/* Placement HOST: copy the PENDING selection's missing pages of the chosen
+ * heads (FKV_HEADS_*) from the host pool into free slots of the GPU page cache.
+ * Slots read by the ACTIVE selection are never written.  Placement HBM: no-op. */
+int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream);
+
+/* o_h = softmax(q_h K^T / sqrt(d)) V over sink + picked pages + window + open
+ * page (Sec. 2.1), the group sharing its KV head's pages.  `use` = FKV_USE_*.
+ * q dev [batch, n_q, d]; out_dev [batch, n_q, d] fp32. */
+int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev,
+                           int32_t use, void* stream);
+
+/* End of step: PENDING becomes ACTIVE, the staged query becomes q_prev (host-side flip). */
+int fkv_commit(fkv_ctx* ctx, int32_t layer);
+
+/* One whole step of one layer in the order of Sec. 3.2-3.3:
+ * append -> correction test -> selection for all heads -> recall for corrected
+ * heads -> attention (corrected heads on the new pages, others on the reused
+ * ones) -> deferred recall for the other heads on copy_stream -> commit.
+ * No host synchronisation.  copy_stream may equal compute_stream. */
+int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev,
+                    const void* v_new_dev, float* out_dev, void* compute_stream, void* copy_stream);
+
+/* ---- introspection for tests (blocking: synchronises the device) --------- */
+#define FKV_DBG_SUMMARIES   0  /* T     [batch, n_kv, 2 (max,min), max_pages, d]      */
+#define FKV_DBG_WEIGHTS     1  /* f32   [batch, n_q, max_pages]  page weights P        */
+#define FKV_DBG_SCORES      2  /* f32   [batch, n_kv, max_pages] pooled scores         */
+#define FKV_DBG_ACTIVE_IDS  3  /* i32   [batch, n_kv, k]                               */
+#define FKV_DBG_PENDING_IDS 4  /* i32   [batch, n_kv, k]                               */
+#define FKV_DBG_FLAGS       5  /* u8    [batch, n_kv]                                  */
+#define FKV_DBG_MISS        6  /* i32   [batch, n_kv, 1 + k]: count, then page ids     */
+#define FKV_DBG_COSINE      7  /* f64   [batch, n_q]                                   */
+int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes);
+
+/* Token-major copy of one page of one (request, KV head): host_out receives
+ * K [p, d] then V [p, d] (2*p*d elements of T).  where: 0 = the HBM store
+ * (placement HBM), 1 = the host pool, 2 = the GPU page-cache slot the ACTIVE
+ * selection holds `page` in (error if it is not picked). */
+int fkv_debug_read_page(fkv_ctx* ctx, int32_t layer, int32_t request, int32_t kv_head,
+                        int32_t page, int32_t where, void* host_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREEKV_H */

@@ -1,0 +1,521 @@
+// Host side of the C ABI: argument checks, arena carving, per-layer state and the
+// stream-ordered schedule of one decode step.  No kernel code here.
+#include "../../include/freekv.h"
+#include "fkv_internal.h"
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace fkv;
+
+namespace {
+
+std::string g_create_error;
+
+struct LayerState {
+  int L = 0;                 // tokens cached
+  int parity = 0;            // which half of the ping-pong buffers is PENDING / staged
+  bool have_prev_q = false;  // q_prev valid
+  bool have_active = false;  // an ACTIVE selection exists
+  bool have_pending = false; // select has run since the last commit
+  bool staged_q = false;     // corr_check has run since the last commit
+  bool have_flags = false;
+  bool offload_outstanding = false;
+  bool recall_outstanding = false;
+  hipEvent_t ev_offload = nullptr;   // last page offload finished
+  hipEvent_t ev_recall = nullptr;    // deferred recall into ACTIVE's slots finished
+};
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  // per layer
+  size_t pool, summ, qprev, ids, slots, flags, miss, cosine, layer_bytes;
+  // per context
+  size_t P, score, part_o, part_ml, dbg_page, ctx_bytes;
+  size_t total;
+  size_t host_layer_bytes, host_total;
+  int units_per_head, ring_base, n_ring, sel_base, max_splits, k, max_pages;
+};
+
+Layout make_layout(const fkv_config& c) {
+  Layout l{};
+  const int n_kv = c.n_kv_heads, n_q = c.n_q_heads, b = c.batch;
+  l.max_pages = c.max_ctx / PG;
+  l.k = (c.budget_tokens - c.sink_tokens - c.window_tokens) / PG;
+  l.ring_base = c.sink_tokens / PG;
+  l.n_ring = c.window_tokens / PG + 2;
+  l.sel_base = l.ring_base + l.n_ring;
+  l.units_per_head = c.placement == FKV_PLACE_HBM ? l.max_pages : l.sel_base + 2 * l.k;
+  l.max_splits = c.sink_tokens / PG + l.k + c.window_tokens / PG + 1;
+  size_t o = 0;
+  l.pool = o;   o += align_up((size_t)b * n_kv * l.units_per_head * UNIT_BYTES);
+  l.summ = o;   o += align_up((size_t)b * n_kv * 2 * l.max_pages * D * 2);
+  l.qprev = o;  o += align_up((size_t)2 * b * n_q * D * 2);
+  l.ids = o;    o += align_up((size_t)2 * b * n_kv * (l.k > 0 ? l.k : 1) * 4);
+  l.slots = o;  o += align_up((size_t)2 * b * n_kv * (l.k > 0 ? l.k : 1) * 4);
+  l.flags = o;  o += align_up((size_t)b * n_kv);
+  l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 2 * l.k) * 4);
+  l.cosine = o; o += align_up((size_t)b * n_q * 8);
+  l.layer_bytes = o;
+  size_t p = 0;
+  l.P = p;       p += align_up((size_t)b * n_q * l.max_pages * 4);
+  l.score = p;   p += align_up((size_t)b * n_kv * l.max_pages * 4);
+  l.part_o = p;  p += align_up((size_t)b * n_kv * l.max_splits * (n_q / n_kv) * D * 4);
+  l.part_ml = p; p += align_up((size_t)b * n_kv * l.max_splits * (n_q / n_kv) * 2 * 4);
+  l.dbg_page = p; p += align_up((size_t)UNIT_BYTES);
+  l.ctx_bytes = p;
+  l.total = l.layer_bytes * c.n_layers + l.ctx_bytes;
+  l.host_layer_bytes = c.placement == FKV_PLACE_HOST ? (size_t)b * n_kv * l.max_pages * UNIT_BYTES : 0;
+  l.host_total = l.host_layer_bytes * c.n_layers;
+  return l;
+}
+
+const char* check_config(const fkv_config* c) {
+  if (!c) return "null config";
+  if (c->n_layers < 1 || c->batch < 1) return "n_layers and batch must be >= 1";
+  if (c->head_dim != D) return "head_dim must be 128";
+  if (c->page_size != PG) return "page_size must be 32";
+  if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
+  if (c->n_q_heads / c->n_kv_heads > MAX_G) return "group size above 8 is not supported";
+  if (c->max_ctx < PG || c->max_ctx % PG) return "max_ctx must be a positive multiple of page_size";
+  if (c->budget_tokens % PG || c->sink_tokens % PG || c->window_tokens % PG) return "budget, sink and window must be multiples of page_size";
+  if (c->sink_tokens < 0 || c->window_tokens < 0 || c->budget_tokens < c->sink_tokens + c->window_tokens) return "budget must cover sink + window";
+  if (c->dtype != FKV_DTYPE_FP16 && c->dtype != FKV_DTYPE_BF16) return "dtype must be fp16 or bf16";
+  if (c->placement != FKV_PLACE_HBM && c->placement != FKV_PLACE_HOST) return "bad placement";
+  if ((size_t)(c->max_ctx / PG) * 4 + 4096 > 65536) return "max_ctx above 503808 tokens is not supported (top-k keys live in LDS)";
+  if ((c->budget_tokens - c->sink_tokens - c->window_tokens) / PG > 1024) return "more than 1024 selectable pages are not supported";
+  if (c->tau != c->tau) return "tau is NaN";
+  return nullptr;
+}
+
+Geom make_geom(const fkv_config& c, int L) {
+  Geom g;
+  g.L = L;
+  g.n_full = L / PG;
+  g.r = L % PG;
+  g.n_sink = c.sink_tokens / PG < g.n_full ? c.sink_tokens / PG : g.n_full;
+  const int rest = g.n_full - g.n_sink;
+  g.n_win = c.window_tokens / PG < rest ? c.window_tokens / PG : rest;
+  g.cand_lo = g.n_sink;
+  g.n_cand = g.n_full - g.n_sink - g.n_win;
+  const int k = (c.budget_tokens - c.sink_tokens - c.window_tokens) / PG;
+  g.k_eff = k < g.n_cand ? k : g.n_cand;
+  return g;
+}
+
+}  // namespace
+
+struct fkv_ctx {
+  fkv_config cfg;
+  Layout lay;
+  Dims dims;
+  char* dev = nullptr;
+  char* host = nullptr;
+  std::vector<LayerState> layers;
+  std::string err;
+  hipEvent_t ev_fork = nullptr;
+
+  char* layer_base(int l) const { return dev + lay.layer_bytes * l; }
+  char* ctx_base() const { return dev + lay.layer_bytes * cfg.n_layers; }
+  PoolDesc pool_desc(int l) const {
+    PoolDesc pd;
+    pd.pool = reinterpret_cast<uint16_t*>(layer_base(l) + lay.pool);
+    pd.units_per_head = lay.units_per_head;
+    pd.placement = cfg.placement;
+    pd.ring_base = lay.ring_base;
+    pd.n_ring = lay.n_ring;
+    pd.sel_base = lay.sel_base;
+    return pd;
+  }
+  uint16_t* summ(int l) const { return reinterpret_cast<uint16_t*>(layer_base(l) + lay.summ); }
+  uint16_t* host_pool(int l) const { return host ? reinterpret_cast<uint16_t*>(host + lay.host_layer_bytes * l) : nullptr; }
+  uint16_t* qprev(int l, int half) const { return reinterpret_cast<uint16_t*>(layer_base(l) + lay.qprev) + (size_t)half * cfg.batch * cfg.n_q_heads * D; }
+  int32_t* ids(int l, int half) const { return reinterpret_cast<int32_t*>(layer_base(l) + lay.ids) + (size_t)half * cfg.batch * cfg.n_kv_heads * (lay.k > 0 ? lay.k : 1); }
+  int32_t* slots(int l, int half) const { return reinterpret_cast<int32_t*>(layer_base(l) + lay.slots) + (size_t)half * cfg.batch * cfg.n_kv_heads * (lay.k > 0 ? lay.k : 1); }
+  uint8_t* flags(int l) const { return reinterpret_cast<uint8_t*>(layer_base(l) + lay.flags); }
+  int32_t* miss(int l) const { return reinterpret_cast<int32_t*>(layer_base(l) + lay.miss); }
+  double* cosine(int l) const { return reinterpret_cast<double*>(layer_base(l) + lay.cosine); }
+  float* P() const { return reinterpret_cast<float*>(ctx_base() + lay.P); }
+  float* score() const { return reinterpret_cast<float*>(ctx_base() + lay.score); }
+  float* part_o() const { return reinterpret_cast<float*>(ctx_base() + lay.part_o); }
+  float* part_ml() const { return reinterpret_cast<float*>(ctx_base() + lay.part_ml); }
+  uint16_t* dbg_page() const { return reinterpret_cast<uint16_t*>(ctx_base() + lay.dbg_page); }
+
+  int fail(int code, const std::string& msg) { err = msg; return code; }
+  int hip_fail(hipError_t e, const char* what) {
+    err = std::string(what) + ": " + hipGetErrorString(e);
+    return FKV_EHIP;
+  }
+};
+
+#define FKV_HIP(ctx, call)                                   \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return (ctx)->hip_fail(e_, #call); \
+  } while (0)
+
+#define FKV_CHECK_LAYER(ctx, layer)                                                  \
+  do {                                                                               \
+    if (!(ctx)) return FKV_EINVAL;                                                   \
+    if ((layer) < 0 || (layer) >= (ctx)->cfg.n_layers) return (ctx)->fail(FKV_ERANGE, "layer out of range"); \
+  } while (0)
+
+// Work of this layer on `st` from here on must see the deferred recall of the previous
+// step finished: it reuses the miss list and flags that recall reads, and the slots it fills.
+static int wait_recall(fkv_ctx* ctx, LayerState& ls, hipStream_t st) {
+  if (ls.recall_outstanding) {
+    hipError_t e = hipStreamWaitEvent(st, ls.ev_recall, 0);
+    if (e != hipSuccess) return ctx->hip_fail(e, "hipStreamWaitEvent");
+    ls.recall_outstanding = false;
+  }
+  return FKV_OK;
+}
+
+static int after_launch(fkv_ctx* ctx, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return ctx->hip_fail(e, what);
+  return FKV_OK;
+}
+
+extern "C" {
+
+int fkv_arena_bytes(const fkv_config* cfg, size_t* dev_bytes, size_t* host_bytes) {
+  const char* why = check_config(cfg);
+  if (why) { g_create_error = why; return FKV_EINVAL; }
+  const Layout l = make_layout(*cfg);
+  if (dev_bytes) *dev_bytes = l.total;
+  if (host_bytes) *host_bytes = l.host_total;
+  return FKV_OK;
+}
+
+int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* host_arena,
+               size_t host_bytes, fkv_ctx** out) {
+  if (!out) { g_create_error = "null out pointer"; return FKV_EINVAL; }
+  *out = nullptr;
+  const char* why = check_config(cfg);
+  if (why) { g_create_error = why; return FKV_EINVAL; }
+  const Layout l = make_layout(*cfg);
+  if (!dev_arena || (reinterpret_cast<uintptr_t>(dev_arena) & 255)) { g_create_error = "device arena null or not 256-byte aligned"; return FKV_EINVAL; }
+  if (dev_bytes < l.total) { g_create_error = "device arena too small"; return FKV_ENOMEM; }
+  if (cfg->placement == FKV_PLACE_HOST) {
+    if (!host_arena || (reinterpret_cast<uintptr_t>(host_arena) & 255)) { g_create_error = "host arena null or not 256-byte aligned"; return FKV_EINVAL; }
+    if (host_bytes < l.host_total) { g_create_error = "host arena too small"; return FKV_ENOMEM; }
+  }
+  fkv_ctx* ctx = new fkv_ctx();
+  ctx->cfg = *cfg;
+  ctx->lay = l;
+  ctx->dims = Dims{cfg->batch, cfg->n_q_heads, cfg->n_kv_heads, cfg->n_q_heads / cfg->n_kv_heads, l.k, l.max_pages, cfg->dtype};
+  ctx->dev = static_cast<char*>(dev_arena);
+  ctx->host = cfg->placement == FKV_PLACE_HOST ? static_cast<char*>(host_arena) : nullptr;
+  ctx->layers.resize(cfg->n_layers);
+  hipError_t e = hipMemset(dev_arena, 0, l.total);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+  for (int i = 0; e == hipSuccess && i < cfg->n_layers; ++i) {
+    e = hipEventCreateWithFlags(&ctx->layers[i].ev_offload, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->layers[i].ev_recall, hipEventDisableTiming);
+  }
+  if (e != hipSuccess) {
+    g_create_error = std::string("HIP failure in fkv_create: ") + hipGetErrorString(e);
+    fkv_destroy(ctx);
+    return FKV_EHIP;
+  }
+  // ids start as "nothing picked"
+  for (int i = 0; i < cfg->n_layers; ++i) {
+    const size_t n = (size_t)2 * cfg->batch * cfg->n_kv_heads * (l.k > 0 ? l.k : 1) * 4;
+    e = hipMemset(ctx->ids(i, 0), 0xff, n);
+    if (e != hipSuccess) break;
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    g_create_error = std::string("HIP failure in fkv_create: ") + hipGetErrorString(e);
+    fkv_destroy(ctx);
+    return FKV_EHIP;
+  }
+  *out = ctx;
+  return FKV_OK;
+}
+
+int fkv_destroy(fkv_ctx* ctx) {
+  if (!ctx) return FKV_EINVAL;
+  (void)hipDeviceSynchronize();
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  for (auto& ls : ctx->layers) {
+    if (ls.ev_offload) (void)hipEventDestroy(ls.ev_offload);
+    if (ls.ev_recall) (void)hipEventDestroy(ls.ev_recall);
+  }
+  delete ctx;
+  return FKV_OK;
+}
+
+const char* fkv_last_error(const fkv_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int fkv_context_len(const fkv_ctx* ctx, int32_t layer) {
+  if (!ctx) return FKV_EINVAL;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return FKV_ERANGE;
+  return ctx->layers[layer].L;
+}
+
+int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* V_dev, int32_t n_tokens, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (n_tokens < 0 || n_tokens > ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "n_tokens exceeds max_ctx");
+  if (n_tokens > 0 && (!K_dev || !V_dev)) return ctx->fail(FKV_EINVAL, "null K or V");
+  LayerState& ls = ctx->layers[layer];
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Geom g = make_geom(ctx->cfg, n_tokens);
+  launch_load_prefix(ctx->dims, ctx->pool_desc(layer), ctx->summ(layer), ctx->host_pool(layer),
+                     static_cast<const uint16_t*>(K_dev), static_cast<const uint16_t*>(V_dev), n_tokens, g, st);
+  int rc = after_launch(ctx, "load_prefix kernel");
+  if (rc) return rc;
+  // a fresh context: no previous query, nothing picked
+  const size_t n = (size_t)2 * ctx->cfg.batch * ctx->cfg.n_kv_heads * (ctx->lay.k > 0 ? ctx->lay.k : 1) * 4;
+  FKV_HIP(ctx, hipMemsetAsync(ctx->ids(layer, 0), 0xff, n, st));
+  ls = LayerState{n_tokens, 0, false, false, false, false, false, false, false, ls.ev_offload, ls.ev_recall};
+  return FKV_OK;
+}
+
+int fkv_kv_append(fkv_ctx* ctx, int32_t layer, const void* k_new_dev, const void* v_new_dev, void* stream, void* copy_stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!k_new_dev || !v_new_dev) return ctx->fail(FKV_EINVAL, "null k_new or v_new");
+  LayerState& ls = ctx->layers[layer];
+  if (ls.L >= ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "append beyond max_ctx");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+  const Geom g = make_geom(ctx->cfg, ls.L + 1);
+  launch_append(ctx->dims, ctx->pool_desc(layer), ctx->summ(layer), static_cast<const uint16_t*>(k_new_dev),
+                static_cast<const uint16_t*>(v_new_dev), g, st);
+  int rc = after_launch(ctx, "append kernel");
+  if (rc) return rc;
+  ls.L += 1;
+  if (ctx->cfg.placement == FKV_PLACE_HOST && g.r == 0) {
+    // the token filled page n_full - 1: offload it (Sec. 4.2) behind the append, on the copy stream
+    if (cs != st) {
+      FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+      FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
+    }
+    launch_offload(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), g.n_full - 1, cs);
+    rc = after_launch(ctx, "offload kernel");
+    if (rc) return rc;
+    FKV_HIP(ctx, hipEventRecord(ls.ev_offload, cs));
+    ls.offload_outstanding = true;
+  }
+  return FKV_OK;
+}
+
+int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int32_t n_pages, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (ctx->cfg.placement != FKV_PLACE_HBM) return ctx->fail(FKV_ESTATE, "summary recompute needs the keys in HBM");
+  LayerState& ls = ctx->layers[layer];
+  const int n_have = (ls.L + PG - 1) / PG;
+  if (first_page < 0 || n_pages < 0 || first_page + n_pages > n_have) return ctx->fail(FKV_ERANGE, "page range beyond the cached context");
+  launch_summary_recompute(ctx->dims, ctx->pool_desc(layer), ctx->summ(layer), first_page, n_pages,
+                           make_geom(ctx->cfg, ls.L), static_cast<hipStream_t>(stream));
+  return after_launch(ctx, "summary kernel");
+}
+
+int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flags_dev, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!q_dev) return ctx->fail(FKV_EINVAL, "null q");
+  LayerState& ls = ctx->layers[layer];
+  int rcw = wait_recall(ctx, ls, static_cast<hipStream_t>(stream));
+  if (rcw) return rcw;
+  launch_corr(ctx->dims, static_cast<const uint16_t*>(q_dev), ctx->qprev(layer, ls.parity ^ 1),
+              ctx->qprev(layer, ls.parity), ls.have_prev_q ? 1 : 0, ctx->cfg.tau, ctx->flags(layer),
+              flags_dev, ctx->cosine(layer), static_cast<hipStream_t>(stream));
+  int rc = after_launch(ctx, "corr kernel");
+  if (rc) return rc;
+  ls.staged_q = true;
+  ls.have_flags = true;
+  return FKV_OK;
+}
+
+int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* page_ids_dev, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!q_dev) return ctx->fail(FKV_EINVAL, "null q");
+  LayerState& ls = ctx->layers[layer];
+  if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Geom g = make_geom(ctx->cfg, ls.L);
+  int rcw = wait_recall(ctx, ls, st);
+  if (rcw) return rcw;
+  launch_score(ctx->dims, ctx->summ(layer), static_cast<const uint16_t*>(q_dev), ctx->P(), g, st);
+  int rc = after_launch(ctx, "score kernel");
+  if (rc) return rc;
+  launch_select(ctx->dims, ctx->P(), ctx->score(), ctx->ids(layer, ls.parity), page_ids_dev, g, st);
+  rc = after_launch(ctx, "select kernel");
+  if (rc) return rc;
+  if (ctx->cfg.placement == FKV_PLACE_HOST) {
+    launch_plan(ctx->dims, ctx->ids(layer, ls.parity), ctx->ids(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity ^ 1),
+                ctx->slots(layer, ls.parity), ctx->miss(layer), st);
+    rc = after_launch(ctx, "plan kernel");
+    if (rc) return rc;
+  }
+  ls.have_pending = true;
+  return FKV_OK;
+}
+
+int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (heads < 0 || heads > 2) return ctx->fail(FKV_EINVAL, "bad heads selector");
+  if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
+  LayerState& ls = ctx->layers[layer];
+  if (!ls.have_pending) return ctx->fail(FKV_ESTATE, "recall before page_select");
+  if (heads != FKV_HEADS_ALL && !ls.have_flags) return ctx->fail(FKV_ESTATE, "recall by flag before corr_check");
+  hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+  if (ls.offload_outstanding) {   // a page offloaded moments ago may be picked already
+    FKV_HIP(ctx, hipStreamWaitEvent(cs, ls.ev_offload, 0));
+  }
+  launch_gather(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ctx->miss(layer), nullptr,
+                ctx->flags(layer), heads, cs);
+  return after_launch(ctx, "gather kernel");
+}
+
+int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev, int32_t use, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!q_dev || !out_dev) return ctx->fail(FKV_EINVAL, "null q or out");
+  if (use < 0 || use > 2) return ctx->fail(FKV_EINVAL, "bad use selector");
+  LayerState& ls = ctx->layers[layer];
+  if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
+  if (use != FKV_USE_ACTIVE && !ls.have_pending) return ctx->fail(FKV_ESTATE, "attention on the pending selection before page_select");
+  if (use == FKV_USE_BY_FLAG && !ls.have_flags) return ctx->fail(FKV_ESTATE, "attention by flag before corr_check");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rcw = wait_recall(ctx, ls, st);
+  if (rcw) return rcw;
+  const Geom g = make_geom(ctx->cfg, ls.L);
+  launch_attn(ctx->dims, ctx->pool_desc(layer), static_cast<const uint16_t*>(q_dev), ctx->ids(layer, ls.parity ^ 1),
+              ctx->ids(layer, ls.parity), ctx->slots(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity),
+              ctx->flags(layer), use, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, out_dev, g, st);
+  return after_launch(ctx, "attention kernels");
+}
+
+int fkv_commit(fkv_ctx* ctx, int32_t layer) {
+  FKV_CHECK_LAYER(ctx, layer);
+  LayerState& ls = ctx->layers[layer];
+  if (!ls.have_pending || !ls.staged_q) return ctx->fail(FKV_ESTATE, "commit needs corr_check and page_select first");
+  ls.parity ^= 1;
+  ls.have_prev_q = true;
+  ls.have_active = true;
+  ls.have_pending = false;
+  ls.staged_q = false;
+  ls.have_flags = false;
+  return FKV_OK;
+}
+
+int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev, const void* v_new_dev,
+                    float* out_dev, void* compute_stream, void* copy_stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!q_dev || !k_new_dev || !v_new_dev || !out_dev) return ctx->fail(FKV_EINVAL, "null argument");
+  LayerState& ls = ctx->layers[layer];
+  hipStream_t st = static_cast<hipStream_t>(compute_stream);
+  hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+  int rc = fkv_kv_append(ctx, layer, k_new_dev, v_new_dev, compute_stream, copy_stream);
+  if (rc) return rc;
+  rc = fkv_corr_check(ctx, layer, q_dev, nullptr, compute_stream);
+  if (rc) return rc;
+  rc = fkv_page_select(ctx, layer, q_dev, nullptr, compute_stream);
+  if (rc) return rc;
+  const bool host_pool = ctx->cfg.placement == FKV_PLACE_HOST;
+  if (host_pool) {
+    // corrected heads: recall before this step's attention (Sec. 3.3)
+    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_FLAGGED, compute_stream);
+    if (rc) return rc;
+  }
+  rc = fkv_sparse_decode_attn(ctx, layer, q_dev, out_dev, FKV_USE_BY_FLAG, compute_stream);
+  if (rc) return rc;
+  if (host_pool) {
+    // other heads: recall for the next step, off the critical path (Sec. 3.2)
+    if (cs != st) {
+      // the copy stream needs the plan (made before attention) and must not start before the
+      // previous deferred recall of this layer has been consumed: both hold once the
+      // compute stream has passed the point recorded here
+      FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+      FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
+    }
+    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
+    if (rc) return rc;
+    FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
+    ls.recall_outstanding = true;
+  }
+  return fkv_commit(ctx, layer);
+}
+
+int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!host_out) return ctx->fail(FKV_EINVAL, "null output");
+  const fkv_config& c = ctx->cfg;
+  const LayerState& ls = ctx->layers[layer];
+  const size_t kk = ctx->lay.k;
+  const void* src = nullptr;
+  size_t n = 0;
+  switch (what) {
+    case FKV_DBG_SUMMARIES:   src = ctx->summ(layer); n = (size_t)c.batch * c.n_kv_heads * 2 * ctx->lay.max_pages * D * 2; break;
+    case FKV_DBG_WEIGHTS:     src = ctx->P(); n = (size_t)c.batch * c.n_q_heads * ctx->lay.max_pages * 4; break;
+    case FKV_DBG_SCORES:      src = ctx->score(); n = (size_t)c.batch * c.n_kv_heads * ctx->lay.max_pages * 4; break;
+    case FKV_DBG_ACTIVE_IDS:  src = ctx->ids(layer, ls.parity ^ 1); n = (size_t)c.batch * c.n_kv_heads * kk * 4; break;
+    case FKV_DBG_PENDING_IDS: src = ctx->ids(layer, ls.parity); n = (size_t)c.batch * c.n_kv_heads * kk * 4; break;
+    case FKV_DBG_FLAGS:       src = ctx->flags(layer); n = (size_t)c.batch * c.n_kv_heads; break;
+    case FKV_DBG_COSINE:      src = ctx->cosine(layer); n = (size_t)c.batch * c.n_q_heads * 8; break;
+    case FKV_DBG_MISS: {
+      n = (size_t)c.batch * c.n_kv_heads * (1 + kk) * 4;
+      if (bytes < n) return ctx->fail(FKV_EINVAL, "output buffer too small");
+      FKV_HIP(ctx, hipDeviceSynchronize());
+      std::vector<int32_t> tmp((size_t)c.batch * c.n_kv_heads * (1 + 2 * kk));
+      FKV_HIP(ctx, hipMemcpy(tmp.data(), ctx->miss(layer), tmp.size() * 4, hipMemcpyDeviceToHost));
+      int32_t* o = static_cast<int32_t*>(host_out);
+      for (int h = 0; h < c.batch * c.n_kv_heads; ++h) {
+        const int32_t* mh = tmp.data() + (size_t)h * (1 + 2 * kk);
+        o[(size_t)h * (1 + kk)] = mh[0];
+        for (size_t i = 0; i < kk; ++i) o[(size_t)h * (1 + kk) + 1 + i] = (int32_t)i < mh[0] ? mh[1 + i] : -1;
+      }
+      return FKV_OK;
+    }
+    default: return ctx->fail(FKV_EINVAL, "unknown debug item");
+  }
+  if (bytes < n) return ctx->fail(FKV_EINVAL, "output buffer too small");
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  if (n) FKV_HIP(ctx, hipMemcpy(host_out, src, n, hipMemcpyDeviceToHost));
+  return FKV_OK;
+}
+
+int fkv_debug_read_page(fkv_ctx* ctx, int32_t layer, int32_t request, int32_t kv_head, int32_t page, int32_t where, void* host_out) {
+  FKV_CHECK_LAYER(ctx, layer);
+  const fkv_config& c = ctx->cfg;
+  if (!host_out) return ctx->fail(FKV_EINVAL, "null output");
+  if (request < 0 || request >= c.batch || kv_head < 0 || kv_head >= c.n_kv_heads) return ctx->fail(FKV_ERANGE, "request or head out of range");
+  const LayerState& ls = ctx->layers[layer];
+  if (page < 0 || page >= (ls.L + PG - 1) / PG) return ctx->fail(FKV_ERANGE, "page beyond the cached context");
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  const size_t head = (size_t)request * c.n_kv_heads + kv_head;
+  const PoolDesc pd = ctx->pool_desc(layer);
+  const uint16_t* unit = nullptr;
+  if (where == 0) {
+    if (c.placement != FKV_PLACE_HBM) return ctx->fail(FKV_ESTATE, "no HBM store in host placement");
+    unit = pd.pool + (head * pd.units_per_head + page) * UNIT_ELEMS;
+  } else if (where == 1) {
+    if (c.placement != FKV_PLACE_HOST) return ctx->fail(FKV_ESTATE, "no host pool in HBM placement");
+    unit = ctx->host_pool(layer) + (head * ctx->lay.max_pages + page) * UNIT_ELEMS;
+  } else if (where == 2) {
+    if (c.placement != FKV_PLACE_HOST) return ctx->fail(FKV_ESTATE, "no page cache in HBM placement");
+    const size_t kk = ctx->lay.k;
+    std::vector<int32_t> idv(kk), slv(kk);
+    FKV_HIP(ctx, hipMemcpy(idv.data(), ctx->ids(layer, ls.parity ^ 1) + head * kk, kk * 4, hipMemcpyDeviceToHost));
+    FKV_HIP(ctx, hipMemcpy(slv.data(), ctx->slots(layer, ls.parity ^ 1) + head * kk, kk * 4, hipMemcpyDeviceToHost));
+    int slot = -1;
+    for (size_t i = 0; i < kk; ++i) if (idv[i] == page) slot = slv[i];
+    if (slot < 0) return ctx->fail(FKV_ERANGE, "page is not in the active selection");
+    unit = pd.pool + (head * pd.units_per_head + pd.sel_base + slot) * UNIT_ELEMS;
+  } else {
+    return ctx->fail(FKV_EINVAL, "bad where");
+  }
+  launch_read_page(unit, ctx->dbg_page(), nullptr);
+  int rc = after_launch(ctx, "read_page kernel");
+  if (rc) return rc;
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  FKV_HIP(ctx, hipMemcpy(host_out, ctx->dbg_page(), UNIT_BYTES, hipMemcpyDeviceToHost));
+  return FKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,290 @@
+// Data-plane kernels: token append with incremental min-max summaries, bulk context
+// load, summary recompute, page offload to / recall from the host pool.
+#include "fkv_internal.h"
+
+namespace fkv {
+
+template <int DT> struct Cvt;
+template <> struct Cvt<0> {   // fp16
+  static __device__ __forceinline__ float f(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+};
+template <> struct Cvt<1> {   // bf16
+  static __device__ __forceinline__ float f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+};
+
+__device__ __forceinline__ int resident_unit(const PoolDesc& pd, int page) {
+  if (pd.placement == 0) return page;
+  return page < pd.ring_base ? page : pd.ring_base + page % pd.n_ring;
+}
+__device__ __forceinline__ size_t head_base(const PoolDesc& pd, int b, int m, int n_kv) {
+  return (size_t)(b * n_kv + m) * pd.units_per_head;
+}
+__device__ __forceinline__ size_t summ_idx(int b, int m, int n_kv, int which, int max_pages, int page) {
+  return ((size_t)((b * n_kv + m) * 2 + which) * max_pages + page) * D;
+}
+
+// ---- append one token: grid (n_kv, batch), 128 threads = channels -------------
+template <int DT>
+__global__ __launch_bounds__(128) void append_kernel(PoolDesc pd, uint16_t* __restrict__ summ,
+                                                     const uint16_t* __restrict__ k_new,
+                                                     const uint16_t* __restrict__ v_new, Geom g,
+                                                     int n_kv, int max_pages) {
+  const int m = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  const int pos = g.L - 1, page = pos / PG, t = pos % PG;
+  const uint16_t kb = k_new[(size_t)(b * n_kv + m) * D + c];
+  const uint16_t vb = v_new[(size_t)(b * n_kv + m) * D + c];
+  uint16_t* unit = pd.pool + (head_base(pd, b, m, n_kv) + resident_unit(pd, page)) * UNIT_ELEMS;
+  unit[k_elem_off(t, c)] = kb;
+  unit[v_elem_off(t, c)] = vb;
+  uint16_t* pmax = summ + summ_idx(b, m, n_kv, 0, max_pages, page) + c;
+  uint16_t* pmin = summ + summ_idx(b, m, n_kv, 1, max_pages, page) + c;
+  if (t == 0) {
+    *pmax = kb;
+    *pmin = kb;
+  } else {
+    const float kf = Cvt<DT>::f(kb);
+    if (kf > Cvt<DT>::f(*pmax)) *pmax = kb;
+    if (kf < Cvt<DT>::f(*pmin)) *pmin = kb;
+  }
+}
+
+// ---- bulk load: grid (n_pages, n_kv, batch), 256 threads ------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void load_prefix_kernel(PoolDesc pd, uint16_t* __restrict__ summ,
+                                                          uint16_t* __restrict__ host_pool,
+                                                          const uint16_t* __restrict__ K,
+                                                          const uint16_t* __restrict__ V, int n_tokens,
+                                                          int n_kv, int max_pages) {
+  __shared__ __attribute__((aligned(16))) uint16_t sk[PG * D];
+  __shared__ __attribute__((aligned(16))) uint16_t sv[PG * D];
+  const int page = blockIdx.x, m = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int n_pages = (n_tokens + PG - 1) / PG;
+  const int nv = min(PG, n_tokens - page * PG);
+  for (int i = tid; i < PG * D / 8; i += 256) {
+    const int t = i >> 4, c8 = i & 15;
+    uint4 kv4 = make_uint4(0, 0, 0, 0), vv4 = make_uint4(0, 0, 0, 0);
+    if (t < nv) {
+      const size_t src = ((size_t)(b * (size_t)n_tokens + page * PG + t) * n_kv + m) * D + c8 * 8;
+      kv4 = *reinterpret_cast<const uint4*>(K + src);
+      vv4 = *reinterpret_cast<const uint4*>(V + src);
+    }
+    *reinterpret_cast<uint4*>(sk + t * D + c8 * 8) = kv4;
+    *reinterpret_cast<uint4*>(sv + t * D + c8 * 8) = vv4;
+  }
+  __syncthreads();
+  // destinations: the HBM unit (if this page is resident there) and the host pool unit
+  uint16_t* dst_gpu = nullptr;
+  uint16_t* dst_host = nullptr;
+  if (pd.placement == 0) {
+    dst_gpu = pd.pool + (head_base(pd, b, m, n_kv) + page) * UNIT_ELEMS;
+  } else {
+    if (page < pd.ring_base || page >= n_pages - pd.n_ring)
+      dst_gpu = pd.pool + (head_base(pd, b, m, n_kv) + resident_unit(pd, page)) * UNIT_ELEMS;
+    dst_host = host_pool + ((size_t)(b * n_kv + m) * max_pages + page) * UNIT_ELEMS;
+  }
+  for (int i = tid; i < UNIT_ELEMS / 8; i += 256) {
+    __attribute__((aligned(16))) uint16_t o[8];
+    if (i < PG * D / 8) {   // K page: 8 consecutive channels of one token
+      const int mm = i & 15, kb = (i >> 4) & 3, j8 = i >> 6;
+      const int t = (j8 & 1) * 16 + mm, ch0 = ((j8 >> 1) * 4 + kb) * 8;
+      *reinterpret_cast<uint4*>(o) = *reinterpret_cast<const uint4*>(sk + t * D + ch0);
+    } else {                // V page: one channel of 8 tokens
+      const int iv = i - PG * D / 8;
+      const int mm = iv & 15, kb = (iv >> 4) & 3, cb = iv >> 6;
+      const int ch = cb * 16 + mm;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int t = (e < 4) ? kb * 4 + e : 16 + kb * 4 + (e - 4);
+        o[e] = sv[t * D + ch];
+      }
+    }
+    const uint4 w = *reinterpret_cast<const uint4*>(o);
+    if (dst_gpu) *reinterpret_cast<uint4*>(dst_gpu + i * 8) = w;
+    if (dst_host) *reinterpret_cast<uint4*>(dst_host + i * 8) = w;
+  }
+  if (tid < D) {
+    uint16_t bmax = sk[tid], bmin = sk[tid];
+    float fmax_ = Cvt<DT>::f(bmax), fmin_ = fmax_;
+    for (int t = 1; t < nv; ++t) {
+      const uint16_t kb = sk[t * D + tid];
+      const float kf = Cvt<DT>::f(kb);
+      if (kf > fmax_) { fmax_ = kf; bmax = kb; }
+      if (kf < fmin_) { fmin_ = kf; bmin = kb; }
+    }
+    summ[summ_idx(b, m, n_kv, 0, max_pages, page) + tid] = bmax;
+    summ[summ_idx(b, m, n_kv, 1, max_pages, page) + tid] = bmin;
+  }
+}
+
+// ---- recompute summaries from stored keys (placement HBM): grid (n_pages, n_kv, batch), 128 threads
+template <int DT>
+__global__ __launch_bounds__(128) void summary_recompute_kernel(PoolDesc pd, uint16_t* __restrict__ summ,
+                                                                int first_page, Geom g, int n_kv,
+                                                                int max_pages) {
+  const int page = first_page + blockIdx.x, m = blockIdx.y, b = blockIdx.z, c = threadIdx.x;
+  const int nv = page < g.n_full ? PG : (page == g.n_full ? g.r : 0);
+  if (nv == 0) return;
+  const uint16_t* unit = pd.pool + (head_base(pd, b, m, n_kv) + page) * UNIT_ELEMS;
+  uint16_t bmax = unit[k_elem_off(0, c)], bmin = bmax;
+  float fmax_ = Cvt<DT>::f(bmax), fmin_ = fmax_;
+  for (int t = 1; t < nv; ++t) {
+    const uint16_t kb = unit[k_elem_off(t, c)];
+    const float kf = Cvt<DT>::f(kb);
+    if (kf > fmax_) { fmax_ = kf; bmax = kb; }
+    if (kf < fmin_) { fmin_ = kf; bmin = kb; }
+  }
+  summ[summ_idx(b, m, n_kv, 0, max_pages, page) + c] = bmax;
+  summ[summ_idx(b, m, n_kv, 1, max_pages, page) + c] = bmin;
+}
+
+// ---- offload a filled page to the host pool: grid (n_kv, batch), 256 threads ------
+__global__ __launch_bounds__(256) void offload_kernel(PoolDesc pd, uint16_t* __restrict__ host_pool,
+                                                      int page, int n_kv, int max_pages) {
+  const int m = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const uint4* src = reinterpret_cast<const uint4*>(
+      pd.pool + (head_base(pd, b, m, n_kv) + resident_unit(pd, page)) * UNIT_ELEMS);
+  uint4* dst = reinterpret_cast<uint4*>(host_pool + ((size_t)(b * n_kv + m) * max_pages + page) * UNIT_ELEMS);
+  uint4 w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = src[tid + i * 256];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) dst[tid + i * 256] = w[i];
+}
+
+// ---- recall: copy missing pages host pool -> free page-cache slots ---------------
+// miss: [batch][n_kv][1 + 2k] = count, then k page ids, then k slots.  grid (k, n_kv, batch), 256 threads.
+__global__ __launch_bounds__(256) void gather_kernel(PoolDesc pd, const uint16_t* __restrict__ host_pool,
+                                                     const int32_t* __restrict__ miss,
+                                                     const uint8_t* __restrict__ flags, int heads, int k,
+                                                     int n_kv, int max_pages) {
+  const int i = blockIdx.x, m = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 2 * k);
+  if (i >= mh[0]) return;
+  if (heads != 0) {
+    const bool flagged = flags[b * n_kv + m] != 0;
+    if ((heads == 1) != flagged) return;
+  }
+  const int page = mh[1 + i], slot = mh[1 + k + i];
+  const uint4* src = reinterpret_cast<const uint4*>(host_pool + ((size_t)(b * n_kv + m) * max_pages + page) * UNIT_ELEMS);
+  uint4* dst = reinterpret_cast<uint4*>(pd.pool + (head_base(pd, b, m, n_kv) + pd.sel_base + slot) * UNIT_ELEMS);
+  uint4 w[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) w[j] = src[tid + j * 256];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dst[tid + j * 256] = w[j];
+}
+
+// ---- recall plan: which picked pages are already cached, where the others go ------
+// A page hits iff it is in the ACTIVE selection (it keeps that slot).  Misses go, in
+// ascending page order, to the lowest-numbered slots the ACTIVE selection does not use.
+// grid (n_kv, batch), 64 threads; pool of 2k slots per head.
+__global__ __launch_bounds__(64) void plan_kernel(const int32_t* __restrict__ new_ids,
+                                                  const int32_t* __restrict__ act_ids,
+                                                  const int32_t* __restrict__ act_slots,
+                                                  int32_t* __restrict__ new_slots,
+                                                  int32_t* __restrict__ miss, int k, int n_kv) {
+  extern __shared__ int32_t sm[];          // used[2k], nslot[k]
+  int32_t* used = sm;
+  int32_t* nslot = sm + 2 * k;
+  const int m = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const size_t hb = (size_t)(b * n_kv + m) * k;
+  int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 2 * k);
+  for (int s = tid; s < 2 * k; s += 64) used[s] = 0;
+  __syncthreads();
+  int n_act = 0;
+  for (int i = tid; i < k; i += 64)
+    if (act_ids[hb + i] >= 0) used[act_slots[hb + i]] = 1;
+  for (int i = 0; i < k; ++i) n_act += (act_ids[hb + i] >= 0);   // ids are ascending, -1 padded at the end
+  __syncthreads();
+  for (int i = tid; i < k; i += 64) {
+    const int id = new_ids[hb + i];
+    int slot = -1;
+    if (id >= 0) {
+      int lo = 0, hi = n_act;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (act_ids[hb + mid] < id) lo = mid + 1; else hi = mid;
+      }
+      slot = (lo < n_act && act_ids[hb + lo] == id) ? act_slots[hb + lo] : -2;   // -2: miss
+    }
+    nslot[i] = slot;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int n_miss = 0, s = 0;
+    for (int i = 0; i < k; ++i) {
+      if (nslot[i] == -2) {
+        while (used[s]) ++s;           // at most k slots are in use, 2k exist
+        nslot[i] = s;
+        mh[1 + n_miss] = new_ids[hb + i];
+        mh[1 + k + n_miss] = s;
+        ++n_miss;
+        ++s;
+      }
+    }
+    mh[0] = n_miss;
+  }
+  __syncthreads();
+  for (int i = tid; i < k; i += 64) new_slots[hb + i] = nslot[i];
+}
+
+// ---- debug: one unit -> token-major K [p, d], V [p, d] ---------------------------
+__global__ __launch_bounds__(256) void read_page_kernel(const uint16_t* __restrict__ unit,
+                                                        uint16_t* __restrict__ out) {
+  for (int i = threadIdx.x; i < PG * D; i += 256) {
+    const int t = i / D, c = i % D;
+    out[i] = unit[k_elem_off(t, c)];
+    out[PG * D + i] = unit[v_elem_off(t, c)];
+  }
+}
+
+// ---- launch wrappers ----------------------------------------------------------------
+void launch_append(const Dims& d, const PoolDesc& pd, uint16_t* summ, const uint16_t* k_new,
+                   const uint16_t* v_new, Geom g, hipStream_t st) {
+  dim3 grid(d.n_kv, d.batch);
+  if (d.dtype == 0) append_kernel<0><<<grid, 128, 0, st>>>(pd, summ, k_new, v_new, g, d.n_kv, d.max_pages);
+  else              append_kernel<1><<<grid, 128, 0, st>>>(pd, summ, k_new, v_new, g, d.n_kv, d.max_pages);
+}
+
+void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint16_t* host_pool,
+                        const uint16_t* K, const uint16_t* V, int n_tokens, Geom g, hipStream_t st) {
+  (void)g;
+  const int n_pages = (n_tokens + PG - 1) / PG;
+  if (n_pages == 0) return;
+  dim3 grid(n_pages, d.n_kv, d.batch);
+  if (d.dtype == 0) load_prefix_kernel<0><<<grid, 256, 0, st>>>(pd, summ, host_pool, K, V, n_tokens, d.n_kv, d.max_pages);
+  else              load_prefix_kernel<1><<<grid, 256, 0, st>>>(pd, summ, host_pool, K, V, n_tokens, d.n_kv, d.max_pages);
+}
+
+void launch_summary_recompute(const Dims& d, const PoolDesc& pd, uint16_t* summ, int first_page,
+                              int n_pages, Geom g, hipStream_t st) {
+  if (n_pages <= 0) return;
+  dim3 grid(n_pages, d.n_kv, d.batch);
+  if (d.dtype == 0) summary_recompute_kernel<0><<<grid, 128, 0, st>>>(pd, summ, first_page, g, d.n_kv, d.max_pages);
+  else              summary_recompute_kernel<1><<<grid, 128, 0, st>>>(pd, summ, first_page, g, d.n_kv, d.max_pages);
+}
+
+void launch_offload(const Dims& d, const PoolDesc& pd, uint16_t* host_pool, int page, hipStream_t st) {
+  dim3 grid(d.n_kv, d.batch);
+  offload_kernel<<<grid, 256, 0, st>>>(pd, host_pool, page, d.n_kv, d.max_pages);
+}
+
+void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
+                 int32_t* new_slots, int32_t* miss, hipStream_t st) {
+  if (d.k == 0) return;
+  dim3 grid(d.n_kv, d.batch);
+  plan_kernel<<<grid, 64, 3 * d.k * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv);
+}
+
+void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
+                   const int32_t*, const uint8_t* flags, int heads, hipStream_t st) {
+  if (d.k == 0) return;
+  dim3 grid(d.k, d.n_kv, d.batch);
+  gather_kernel<<<grid, 256, 0, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, d.max_pages);
+}
+
+void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st) {
+  read_page_kernel<<<1, 256, 0, st>>>(unit, out_token_major);
+}
+
+}  // namespace fkv

@@ -1,0 +1,80 @@
+// Internal declarations shared by the host API and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fkv {
+
+constexpr int D = 128;            // head_dim
+constexpr int PG = 32;            // page size p
+constexpr int UNIT_ELEMS = 2 * PG * D;        // K page then V page of one (page, KV head)
+constexpr int UNIT_BYTES = UNIT_ELEMS * 2;    // 16 KiB, the contiguous recall unit (Sec. 4.2)
+constexpr int MAX_G = 8;
+
+// Geometry of the budget at the current context length (Sec. 2.1: B, S, W).
+struct Geom {
+  int L;        // tokens cached, the appended one included
+  int n_full;   // full pages
+  int r;        // tokens in the open page
+  int n_sink;   // sink pages [0, n_sink)
+  int n_win;    // window pages [n_full - n_win, n_full)
+  int cand_lo;  // candidate pages [cand_lo, cand_lo + n_cand)
+  int n_cand;
+  int k_eff;    // pages picked per KV head = min(k, n_cand)
+};
+
+// Where a KV head's pages live in HBM.  Unit u of head (b, m) starts at
+// pool + ((b * n_kv + m) * units_per_head + u) * UNIT_ELEMS.
+struct PoolDesc {
+  uint16_t* pool;
+  int units_per_head;
+  int placement;     // 0: unit = page id.  1: sink page i -> unit i, window/open page j -> ring_base + j % n_ring,
+  int ring_base;     //    picked page in slot s -> sel_base + s
+  int n_ring;
+  int sel_base;
+};
+
+// ---- element offsets inside a unit -------------------------------------
+// K page: [s*2+mb (8)][kb (4)][m (16)][e (8)] with channel = (s*4+kb)*8 + e, token = mb*16 + m.
+// Each group of 512 elements (1 KiB) is one operand load of the 16x16x32 MFMA
+// computing S^T = K Q^T: lane (kb*16 + m) reads 8 consecutive channels of token m.
+__host__ __device__ inline int k_elem_off(int t, int ch) {
+  int s = ch >> 5, kb = (ch >> 3) & 3, e = ch & 7, mb = t >> 4, m = t & 15;
+  return ((((s * 2 + mb) * 4 + kb) * 16 + m) * 8) + e;
+}
+// V page: [cb (8)][kb (4)][m (16)][e (8)] with channel = cb*16 + m and
+// token = (e < 4) ? kb*4 + e : 16 + kb*4 + (e - 4): the token order in which the
+// S^T accumulators of a lane come out, so P feeds the second MFMA from registers.
+__host__ __device__ inline int v_elem_off(int t, int ch) {
+  int cb = ch >> 4, m = ch & 15, hi = t >> 4, kb = (t & 15) >> 2, e = (t & 3) + 4 * hi;
+  return PG * D + (((cb * 4 + kb) * 16 + m) * 8) + e;
+}
+
+// ---- launch wrappers (defined in the kernel files) ----------------------
+struct Dims { int batch, n_q, n_kv, G, k, max_pages, dtype; };
+
+void launch_append(const Dims& d, const PoolDesc& pd, uint16_t* summ, const uint16_t* k_new,
+                   const uint16_t* v_new, Geom g, hipStream_t st);
+void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint16_t* host_pool,
+                        const uint16_t* K, const uint16_t* V, int n_tokens, Geom g, hipStream_t st);
+void launch_summary_recompute(const Dims& d, const PoolDesc& pd, uint16_t* summ, int first_page,
+                              int n_pages, Geom g, hipStream_t st);
+void launch_offload(const Dims& d, const PoolDesc& pd, uint16_t* host_pool, int page, hipStream_t st);
+void launch_corr(const Dims& d, const uint16_t* q, const uint16_t* q_prev, uint16_t* q_stage,
+                 int have_prev, float tau, uint8_t* flags, uint8_t* flags_user, double* cosine,
+                 hipStream_t st);
+void launch_score(const Dims& d, const uint16_t* summ, const uint16_t* q, float* P, Geom g, hipStream_t st);
+void launch_select(const Dims& d, const float* P, float* score, int32_t* ids, int32_t* ids_user,
+                   Geom g, hipStream_t st);
+void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
+                 int32_t* new_slots, int32_t* miss, hipStream_t st);
+void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
+                   const int32_t* new_slots_unused, const uint8_t* flags, int heads, hipStream_t st);
+// returns the number of splits written per KV head
+int  launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
+                 const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,
+                 const uint8_t* flags, int use, float* part_o, float* part_ml, int max_splits,
+                 float* out, Geom g, hipStream_t st);
+void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st);
+
+}  // namespace fkv

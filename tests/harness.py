@@ -1,0 +1,134 @@
+"""Side-by-side driver for the parity tests: the HIP path (through the C ABI binding) and the
+CPU oracle consume the same seeded inputs; every step is compared."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2505_13109_amd as fkv
+from paper_2505_13109_amd import binding as B
+import workloads as W
+from oracle import freekv_oracle as O
+
+TOL_OUT = 2e-3     # max relative error of attention outputs, per head: |d|_inf / |ref|_inf
+
+
+def to_dev(bits: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    return t.view(torch.float16 if dtype == "fp16" else torch.bfloat16)
+
+
+def rel_err_per_head(got: np.ndarray, ref: np.ndarray) -> np.ndarray:
+    d = np.abs(got.astype(np.float64) - ref).max(axis=-1)
+    return d / np.abs(ref).max(axis=-1)
+
+
+class Pair:
+    """One HIP context and the matching oracles for `layers` x `batch` of a workload."""
+
+    def __init__(self, wl, layers, ctx=None, placement=None, tau=None, max_ctx=None, steps=None):
+        self.wl = wl
+        self.layers = list(layers)
+        self.n_ctx = wl.ctx if ctx is None else ctx
+        self.steps = wl.steps if steps is None else steps
+        self.placement = wl.placement if placement is None else placement
+        self.tau = wl.tau if tau is None else tau
+        p = wl.page_size
+        self.max_ctx = max_ctx or ((self.n_ctx + self.steps + p - 1) // p) * p
+        self.g = fkv.FreeKV(n_layers=len(self.layers), batch=wl.batch, n_q_heads=wl.n_q_heads,
+                            n_kv_heads=wl.n_kv_heads, max_ctx=self.max_ctx, budget=wl.budget,
+                            sink=wl.sink, window=wl.window, tau=self.tau, dtype=wl.dtype,
+                            placement=self.placement)
+        self.oracles = {}
+        self.q, self.kd, self.vd = {}, {}, {}
+        self.copy_stream = torch.cuda.Stream()
+        for li, layer in enumerate(self.layers):
+            Kb_all, Vb_all = [], []
+            for r in range(wl.batch):
+                (K, Kb), (V, Vb) = W.kv_prefix(wl, layer, r, self.n_ctx)
+                o = O.FreeKVOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, p, wl.budget, wl.sink,
+                                   wl.window, self.tau, self.max_ctx)
+                o.load_prefix_bulk(K, V)
+                self.oracles[(li, r)] = o
+                Kb_all.append(Kb)
+                Vb_all.append(Vb)
+                self.q[(li, r)] = W.query_stream(wl, layer, r, self.steps)
+                self.kd[(li, r)], self.vd[(li, r)] = W.kv_decode_tokens(wl, layer, r, self.steps)
+            if self.n_ctx:
+                self.g.load_prefix(li, to_dev(np.stack(Kb_all), wl.dtype), to_dev(np.stack(Vb_all), wl.dtype))
+        torch.cuda.synchronize()
+        self.out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda")
+        self.stats = dict(max_rel=0.0, flagged=0, heads=0, misses=0, picked=0)
+
+    def step_inputs(self, li, t):
+        wl = self.wl
+        qb = np.stack([self.q[(li, r)][1][t] for r in range(wl.batch)])
+        kb = np.stack([self.kd[(li, r)][1][t] for r in range(wl.batch)])
+        vb = np.stack([self.vd[(li, r)][1][t] for r in range(wl.batch)])
+        return to_dev(qb, wl.dtype), to_dev(kb, wl.dtype), to_dev(vb, wl.dtype)
+
+    def check_summaries(self, li):
+        wl = self.wl
+        s = W.decode(self.g.debug_read(li, B.DBG_SUMMARIES), wl.dtype)
+        for r in range(wl.batch):
+            o = self.oracles[(li, r)]
+            n_page = (o.L + wl.page_size - 1) // wl.page_size
+            assert np.array_equal(s[r, :, 0, :n_page, :], o.kmax[:n_page].transpose(1, 0, 2)), "kmax"
+            assert np.array_equal(s[r, :, 1, :n_page, :], o.kmin[:n_page].transpose(1, 0, 2)), "kmin"
+
+    def step(self, li, t, check=True, deep=True):
+        """One decode step of layer index li on both sides; returns the oracle results per request."""
+        wl = self.wl
+        q, k, v = self.step_inputs(li, t)
+        self.g.decode_step(li, q, k, v, self.out, copy_stream=self.copy_stream)
+        res = []
+        for r in range(wl.batch):
+            res.append(self.oracles[(li, r)].step(self.q[(li, r)][0][t], self.kd[(li, r)][0][t], self.vd[(li, r)][0][t]))
+        if not check:
+            return res
+        ids = self.g.debug_read(li, B.DBG_ACTIVE_IDS)        # after commit the step's selection is ACTIVE
+        flags = self.g.debug_read(li, B.DBG_FLAGS)
+        out = self.out.cpu().numpy()
+        if deep:
+            Pw = self.g.debug_read(li, B.DBG_WEIGHTS)
+            Sc = self.g.debug_read(li, B.DBG_SCORES)
+            cosv = self.g.debug_read(li, B.DBG_COSINE)
+        if self.placement == 1:
+            miss = self.g.debug_read(li, B.DBG_MISS)
+        for r in range(wl.batch):
+            ref = res[r]
+            gm = ref["geom"]
+            tag = f"layer {self.layers[li]} step {t} request {r} L {gm.L}"
+            if deep:
+                lo, hi = gm.cand_lo, gm.cand_lo + gm.n_cand
+                assert np.array_equal(Pw[r, :, lo:hi], ref["P"]), f"page weights differ: {tag}"
+                assert np.array_equal(Sc[r, :, lo:hi], ref["score"]), f"pooled scores differ: {tag}"
+                if t > 0:
+                    np.testing.assert_allclose(cosv[r], ref["cosine"], rtol=0, atol=1e-12, err_msg=tag)
+            assert np.array_equal(flags[r], ref["flags"]), f"flags differ: {tag}: {flags[r]} vs {ref['flags']}"
+            assert np.array_equal(ids[r], ref["new_ids"]), f"page ids differ: {tag}"
+            err = rel_err_per_head(out[r], ref["out"])
+            assert err.max() <= TOL_OUT, f"attention output off by {err.max():.3e}: {tag}"
+            self.stats["max_rel"] = max(self.stats["max_rel"], float(err.max()))
+            self.stats["flagged"] += int(ref["flags"].sum())
+            self.stats["heads"] += wl.n_kv_heads
+            if self.placement == 1:
+                for m in range(wl.n_kv_heads):
+                    n = int(miss[r, m, 0])
+                    assert sorted(miss[r, m, 1:1 + n].tolist()) == ref["miss"][m], f"miss list differs: {tag} head {m}"
+                    self.stats["misses"] += n
+                    self.stats["picked"] += int((ref["new_ids"][m] >= 0).sum())
+        return res
+
+    def check_cached_pages(self, li, r, m, where):
+        """Bytes of the picked pages where the HIP side keeps them == the bytes appended (oracle's K, V)."""
+        wl = self.wl
+        o = self.oracles[(li, r)]
+        p = wl.page_size
+        for page in [int(j) for j in o.active[m] if j >= 0]:
+            got = W.decode(self.g.debug_read_page(li, r, m, page, where), wl.dtype)
+            assert np.array_equal(got[0], o.K[page * p:(page + 1) * p, m, :]), f"K bytes page {page}"
+            assert np.array_equal(got[1], o.V[page * p:(page + 1) * p, m, :]), f"V bytes page {page}"
+
+    def close(self):
+        self.g.close()
