@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the FreeKV retrieval-decode path on one MI355X.
+
+Workload (`config.workload`): the Llama-3-8B-shaped decode of the second BASELINE config --
+32 layers, 32 query / 8 KV heads, head_dim 128, bf16, batch 1, 32768 cached tokens, page 32,
+budget 2048 (sink = window = 512), tau 0.8, step-correlated queries (rho = 0.9), KV resident
+in HBM.  One "step" is one decode step: fkv_decode_step for each of the 32 layers, i.e. every
+row of the hot path (append + summary update, correction test, page weights, softmax-mean
+top-k, speculative reuse / correction, sparse attention) 32 times.  All inputs are generated
+on the GPU beforehand and are resident in HBM when the timed region starts.
+
+Prints one JSON line; see the field notes in the design doc.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per launch of the split attention kernel at this workload, from
+# `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs scaled by a copy kernel of known
+# size (profiles/attn_kernel_c2_pmc.txt).  None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes(wl):
+    """Per layer-step: page summaries read by the scoring kernel and K/V read by attention."""
+    n_full = wl.ctx // wl.page_size
+    n_cand = n_full - wl.sink // wl.page_size - wl.window // wl.page_size
+    score = n_cand * wl.n_kv_heads * wl.batch * 2 * wl.head_dim * 2
+    pages = wl.budget // wl.page_size + 1          # sink + picked + window + the open page
+    attn = pages * wl.n_kv_heads * wl.batch * 2 * wl.page_size * wl.head_dim * 2
+    return score, attn
+
+
+def gen_inputs(torch, wl, n_steps, device):
+    """Seeded synthetic tensors on the GPU: N(0,1) K/V with 4 outlier channels x8, AR(1) queries."""
+    g = torch.Generator(device=device)
+    g.manual_seed(wl.seed)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float16
+    outl = [7, 43, 71, 101]
+
+    def kv(shape):
+        x = torch.randn(shape, generator=g, device=device, dtype=torch.float32)
+        x[..., outl] *= 8.0
+        return x.to(dt)
+
+    noise = torch.randn((n_steps, wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), generator=g,
+                        device=device, dtype=torch.float32)
+    q = torch.empty_like(noise)
+    state = noise[0].clone()
+    q[0] = state
+    for t in range(1, n_steps):
+        state = wl.rho * state + wl.q_noise * noise[t]
+        q[t] = state
+    q = q.to(dt).contiguous()
+    k_new = kv((n_steps, wl.n_layers, wl.batch, wl.n_kv_heads, wl.head_dim)).contiguous()
+    v_new = kv((n_steps, wl.n_layers, wl.batch, wl.n_kv_heads, wl.head_dim)).contiguous()
+    return kv, q, k_new, v_new
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands, one thread, on a bounded sample: one layer of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    import workloads as W
+    from oracle import freekv_oracle as O
+    with threadpool_limits(limits=1):
+        (K, _), (V, _) = W.kv_prefix(wl, 0, 0)
+        n_max = 400
+        o = O.FreeKVOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.page_size, wl.budget, wl.sink,
+                           wl.window, wl.tau, wl.ctx + n_max + wl.page_size)
+        o.load_prefix_bulk(K, V)
+        q, _ = W.query_stream(wl, 0, 0, n_max)
+        (k, _), (v, _) = W.kv_decode_tokens(wl, 0, 0, n_max)
+        o.step(q[0], k[0], v[0])             # first step corrects every head: not representative, untimed
+        t0 = time.perf_counter()
+        n = 0
+        while n + 1 < n_max and time.perf_counter() - t0 < budget_s:
+            o.step(q[n + 1], k[n + 1], v[n + 1])
+            n += 1
+        dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "layer-steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"layer 0 of the same workload, {n} decode steps after one untimed step, NumPy oracle, 1 thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards over KV heads / requests "
+              "with no exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_13109_amd as fkv
+    import workloads as W
+
+    wl = W.get_workload(args.workload)
+    K, Wm = args.steps, args.warmup
+    n_steps = K + Wm
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = wl.page_size
+    max_ctx = ((wl.ctx + 2 * n_steps + p - 1) // p) * p       # the steps are run twice (timed, then with kernel timers)
+    ctx = fkv.FreeKV(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                     max_ctx=max_ctx, budget=wl.budget, sink=wl.sink, window=wl.window, tau=wl.tau,
+                     dtype=wl.dtype, placement=wl.placement)
+    kv, q, k_new, v_new = gen_inputs(torch, wl, n_steps, dev)
+    for layer in range(wl.n_layers):
+        Kp = kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim))
+        Vp = kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim))
+        ctx.load_prefix(layer, Kp, Vp)
+        torch.cuda.synchronize()
+        del Kp, Vp
+    out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    copy_stream = torch.cuda.Stream()
+
+    def run(t0, t1):
+        for t in range(t0, t1):
+            for layer in range(wl.n_layers):
+                ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer],
+                                stream=stream, copy_stream=copy_stream)
+
+    run(0, Wm)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    run(Wm, n_steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+    assert torch.isfinite(out).all()
+
+    # second pass over the same step inputs with a HIP event pair around every launch of the
+    # split attention kernel (the dominant HBM reader), on the stream it is launched on
+    ctx.profile_enable(K * wl.n_layers)
+    run(Wm, n_steps)
+    attn_ms, attn_n = ctx.profile_read()
+    ctx.profile_enable(0)
+
+    layer_steps = K * wl.n_layers
+    score_b, attn_b = algorithmic_bytes(wl)
+    attn_s = attn_ms / 1e3 / max(attn_n, 1)
+    achieved = attn_b / attn_s / 1e9
+    res = {
+        "metric": "retrieval-decode layer-steps/s at 32K ctx",
+        "value": layer_steps / elapsed,
+        "unit": "layer-steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": elapsed / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_layers} layers, {wl.n_q_heads}q/{wl.n_kv_heads}kv heads, d128, "
+                               f"{wl.dtype}, batch {wl.batch}, ctx {wl.ctx}, page {p}, budget {wl.budget} "
+                               f"(sink {wl.sink}, window {wl.window}), tau {wl.tau}, rho {wl.rho}, "
+                               f"KV {'in HBM' if wl.placement == 0 else 'in pinned host memory'}",
+                   "layer_steps_per_step": wl.n_layers,
+                   "us_per_layer_step": elapsed / layer_steps * 1e6,
+                   "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "attn_kernel (split sparse decode attention)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "algorithmic_bytes_per_launch": attn_b, "avg_launch_us": attn_s * 1e6,
+                     "launches_timed": attn_n},
+    }
+    ctx.close()
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

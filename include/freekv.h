@@ -155,6 +155,14 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer);
 int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev,
                     const void* v_new_dev, float* out_dev, void* compute_stream, void* copy_stream);
 
+/* ---- per-kernel timers ---------------------------------------------------- */
+/* Time the split attention kernel (the dominant HBM reader of the step) with a
+ * HIP event pair around each of the next max_launches launches, on the stream it
+ * is launched on.  max_launches = 0 switches the timers off.  Blocking. */
+int fkv_profile_enable(fkv_ctx* ctx, int32_t max_launches);
+/* Sum of the recorded durations (ms) and their number; resets the timers.  Blocking. */
+int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches);
+
 /* ---- introspection for tests (blocking: synchronises the device) --------- */
 #define FKV_DBG_SUMMARIES   0  /* T     [batch, n_kv, 2 (max,min), max_pages, d]      */
 #define FKV_DBG_WEIGHTS     1  /* f32   [batch, n_q, max_pages]  page weights P        */

@@ -5,6 +5,9 @@ import ctypes as C
 import os
 
 import numpy as np
+# PyTorch supplies device memory and streams, so the library must share its HIP runtime:
+# torch is imported first and libfreekv.so then binds to the libamdhip64 already loaded.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -18,7 +21,7 @@ EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page",
+    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read",
 )
 
 
@@ -69,6 +72,8 @@ def lib() -> C.CDLL:
         "fkv_sparse_decode_attn": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_commit": (C.c_int, [vp, i32]),
         "fkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
+        "fkv_profile_enable": (C.c_int, [vp, i32]),
+        "fkv_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "fkv_debug_read": (C.c_int, [vp, i32, i32, vp, sz]),
         "fkv_debug_read_page": (C.c_int, [vp, i32, i32, i32, i32, i32, vp]),
     }
@@ -175,6 +180,14 @@ class FreeKV:
         s = _stream(stream)
         cs = s if copy_stream is None else _stream(copy_stream)
         self._check(self.L.fkv_decode_step(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), s, cs), "fkv_decode_step")
+
+    def profile_enable(self, max_launches):
+        self._check(self.L.fkv_profile_enable(self._h, max_launches), "fkv_profile_enable")
+
+    def profile_read(self):
+        ms, n = C.c_double(), C.c_int32()
+        self._check(self.L.fkv_profile_read(self._h, C.byref(ms), C.byref(n)), "fkv_profile_read")
+        return ms.value, n.value
 
     # -- introspection ----------------------------------------------------------
     def debug_read(self, layer, what):

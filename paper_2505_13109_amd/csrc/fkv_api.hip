@@ -117,6 +117,10 @@ struct fkv_ctx {
   std::vector<LayerState> layers;
   std::string err;
   hipEvent_t ev_fork = nullptr;
+  // optional timers around the split attention kernel (fkv_profile_*)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;   // begin/end pairs
+  size_t prof_used = 0;
 
   char* layer_base(int l) const { return dev + lay.layer_bytes * l; }
   char* ctx_base() const { return dev + lay.layer_bytes * cfg.n_layers; }
@@ -243,6 +247,7 @@ int fkv_destroy(fkv_ctx* ctx) {
   if (!ctx) return FKV_EINVAL;
   (void)hipDeviceSynchronize();
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   for (auto& ls : ctx->layers) {
     if (ls.ev_offload) (void)hipEventDestroy(ls.ev_offload);
     if (ls.ev_recall) (void)hipEventDestroy(ls.ev_recall);
@@ -385,9 +390,14 @@ int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float
   int rcw = wait_recall(ctx, ls, st);
   if (rcw) return rcw;
   const Geom g = make_geom(ctx->cfg, ls.L);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (ctx->prof_on && ctx->prof_used + 2 <= ctx->prof_ev.size()) {
+    e0 = ctx->prof_ev[ctx->prof_used++];
+    e1 = ctx->prof_ev[ctx->prof_used++];
+  }
   launch_attn(ctx->dims, ctx->pool_desc(layer), static_cast<const uint16_t*>(q_dev), ctx->ids(layer, ls.parity ^ 1),
               ctx->ids(layer, ls.parity), ctx->slots(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity),
-              ctx->flags(layer), use, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, out_dev, g, st);
+              ctx->flags(layer), use, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, out_dev, g, st, e0, e1);
   return after_launch(ctx, "attention kernels");
 }
 
@@ -440,6 +450,35 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     ls.recall_outstanding = true;
   }
   return fkv_commit(ctx, layer);
+}
+
+int fkv_profile_enable(fkv_ctx* ctx, int32_t max_launches) {
+  if (!ctx) return FKV_EINVAL;
+  if (max_launches < 0 || max_launches > (1 << 20)) return ctx->fail(FKV_EINVAL, "max_launches out of range");
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  ctx->prof_used = 0;
+  ctx->prof_on = max_launches > 0;
+  while (ctx->prof_ev.size() < (size_t)2 * max_launches) {
+    hipEvent_t e;
+    FKV_HIP(ctx, hipEventCreate(&e));
+    ctx->prof_ev.push_back(e);
+  }
+  return FKV_OK;
+}
+
+int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches) {
+  if (!ctx || !total_ms || !launches) return FKV_EINVAL;
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  double sum = 0.0;
+  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+    float ms = 0.f;
+    FKV_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[i], ctx->prof_ev[i + 1]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int32_t)(ctx->prof_used / 2);
+  ctx->prof_used = 0;
+  return FKV_OK;
 }
 
 int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes) {

@@ -10,6 +10,7 @@
 // tokens the same lane must supply as the B operand of the second product (the V page
 // is stored in that token order).  Nothing goes through LDS inside the page loop.
 #include "fkv_internal.h"
+#include <cstdlib>
 
 namespace fkv {
 
@@ -250,21 +251,27 @@ static void launch_attn_dt(int nw, dim3 grid, hipStream_t st, PoolDesc pd, const
   else              attn_kernel<DT, 4><<<grid, 256, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d.n_q, d.n_kv, d.G, d.k);
 }
 
+// tuning knob for experiments: pages per block (0 = choose from the shape)
+static int g_pps_override = [] { const char* e = getenv("FKV_ATTN_PPS"); return e ? atoi(e) : 0; }();
+
 int launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
                 const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,
                 const uint8_t* flags, int use, float* part_o, float* part_ml, int max_splits,
-                float* out, Geom g, hipStream_t st) {
+                float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
   // pages per block: aim at >= ~2 blocks per compute unit, at most 4 waves per block
   const int heads = d.n_kv * d.batch;
   int pps = 1;
-  while (pps < 16 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 512) pps *= 2;
+  while (pps < 16 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 256) pps *= 2;
+  if (g_pps_override > 0) pps = g_pps_override;
   while ((n_att + pps - 1) / pps > max_splits) pps *= 2;
   const int n_splits = (n_att + pps - 1) / pps;
   const int nw = pps >= 4 ? 4 : pps;
   dim3 grid(n_splits, d.n_kv, d.batch);
+  if (ev_begin) (void)hipEventRecord(ev_begin, st);
   if (d.dtype == 0) launch_attn_dt<0>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d);
   else              launch_attn_dt<1>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d);
+  if (ev_end) (void)hipEventRecord(ev_end, st);
   dim3 mgrid(d.n_q, d.batch);
   merge_kernel<<<mgrid, 128, 0, st>>>(part_o, part_ml, max_splits, n_splits, out, d.n_q, d.n_kv, d.G);
   return n_splits;

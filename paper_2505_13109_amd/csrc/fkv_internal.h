@@ -74,7 +74,7 @@ void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool,
 int  launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
                  const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,
                  const uint8_t* flags, int use, float* part_o, float* part_ml, int max_splits,
-                 float* out, Geom g, hipStream_t st);
+                 float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st);
 
 }  // namespace fkv
