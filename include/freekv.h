@@ -163,6 +163,13 @@ int fkv_profile_enable(fkv_ctx* ctx, int32_t max_launches);
 /* Sum of the recorded durations (ms) and their number; resets the timers.  Blocking. */
 int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches);
 
+/* Launch the attention kernel `reps` times for every layer in turn (ACTIVE selection, the
+ * state is not changed), back to back on `stream` between one HIP event pair, and return
+ * the elapsed time and the number of launches.  q_dev: layer l's queries at
+ * q_dev + l * q_layer_stride bytes.  out_dev: [batch, n_q, d] fp32 scratch output.  Blocking. */
+int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, float* out_dev, int32_t reps,
+                     void* stream, double* total_ms, int32_t* launches);
+
 /* ---- introspection for tests (blocking: synchronises the device) --------- */
 #define FKV_DBG_SUMMARIES   0  /* T     [batch, n_kv, 2 (max,min), max_pages, d]      */
 #define FKV_DBG_WEIGHTS     1  /* f32   [batch, n_q, max_pages]  page weights P        */
@@ -172,6 +179,8 @@ int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches);
 #define FKV_DBG_FLAGS       5  /* u8    [batch, n_kv]                                  */
 #define FKV_DBG_MISS        6  /* i32   [batch, n_kv, 1 + k]: count, then page ids     */
 #define FKV_DBG_COSINE      7  /* f64   [batch, n_q]                                   */
+#define FKV_DBG_TSTAMP      8  /* i64   [64] 100 MHz phase timestamps of head 0, recorded when the
+                                  context was created with FKV_TSTAMP=1 in the environment     */
 int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes);
 
 /* Token-major copy of one page of one (request, KV head): host_out receives

@@ -15,13 +15,13 @@ FKV_DTYPE_FP16, FKV_DTYPE_BF16 = 0, 1
 FKV_PLACE_HBM, FKV_PLACE_HOST = 0, 1
 FKV_USE_ACTIVE, FKV_USE_PENDING, FKV_USE_BY_FLAG = 0, 1, 2
 FKV_HEADS_ALL, FKV_HEADS_FLAGGED, FKV_HEADS_UNFLAGGED = 0, 1, 2
-DBG_SUMMARIES, DBG_WEIGHTS, DBG_SCORES, DBG_ACTIVE_IDS, DBG_PENDING_IDS, DBG_FLAGS, DBG_MISS, DBG_COSINE = range(8)
+DBG_SUMMARIES, DBG_WEIGHTS, DBG_SCORES, DBG_ACTIVE_IDS, DBG_PENDING_IDS, DBG_FLAGS, DBG_MISS, DBG_COSINE, DBG_TSTAMP = range(9)
 
 EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read",
+    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn",
 )
 
 
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         "fkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
         "fkv_profile_enable": (C.c_int, [vp, i32]),
         "fkv_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
+        "fkv_profile_attn": (C.c_int, [vp, vp, sz, vp, i32, vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "fkv_debug_read": (C.c_int, [vp, i32, i32, vp, sz]),
         "fkv_debug_read_page": (C.c_int, [vp, i32, i32, i32, i32, i32, vp]),
     }
@@ -189,6 +190,14 @@ class FreeKV:
         self._check(self.L.fkv_profile_read(self._h, C.byref(ms), C.byref(n)), "fkv_profile_read")
         return ms.value, n.value
 
+    def profile_attn(self, q_layers, out, reps, stream=None):
+        """q_layers: [n_layers, batch, n_q, d] contiguous; returns (total_ms, launches)."""
+        ms, n = C.c_double(), C.c_int32()
+        stride = q_layers.stride(0) * q_layers.element_size()
+        self._check(self.L.fkv_profile_attn(self._h, _ptr(q_layers), stride, _ptr(out), reps, _stream(stream),
+                                            C.byref(ms), C.byref(n)), "fkv_profile_attn")
+        return ms.value, n.value
+
     # -- introspection ----------------------------------------------------------
     def debug_read(self, layer, what):
         c = self.cfg
@@ -201,6 +210,7 @@ class FreeKV:
             DBG_FLAGS: ((c.batch, c.n_kv_heads), np.uint8),
             DBG_MISS: ((c.batch, c.n_kv_heads, 1 + self.k), np.int32),
             DBG_COSINE: ((c.batch, c.n_q_heads), np.float64),
+            DBG_TSTAMP: ((64,), np.int64),
         }
         shape, dt = shapes[what]
         out = np.empty(shape, dtype=dt)

@@ -4,6 +4,7 @@
 #include "fkv_internal.h"
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -32,9 +33,9 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
   // per layer
-  size_t pool, summ, qprev, ids, slots, flags, miss, cosine, layer_bytes;
+  size_t pool, summ, qprev, ids, slots, flags, miss, cosine, counters, layer_bytes;
   // per context
-  size_t P, score, part_o, part_ml, dbg_page, ctx_bytes;
+  size_t P, score, part_o, part_ml, dbg_page, tstamp, ctx_bytes;
   size_t total;
   size_t host_layer_bytes, host_total;
   int units_per_head, ring_base, n_ring, sel_base, max_splits, k, max_pages;
@@ -59,6 +60,7 @@ Layout make_layout(const fkv_config& c) {
   l.flags = o;  o += align_up((size_t)b * n_kv);
   l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 2 * l.k) * 4);
   l.cosine = o; o += align_up((size_t)b * n_q * 8);
+  l.counters = o; o += align_up((size_t)2 * b * n_kv * 4);   // last-block counters: selection, attention
   l.layer_bytes = o;
   size_t p = 0;
   l.P = p;       p += align_up((size_t)b * n_q * l.max_pages * 4);
@@ -66,6 +68,7 @@ Layout make_layout(const fkv_config& c) {
   l.part_o = p;  p += align_up((size_t)b * n_kv * l.max_splits * (n_q / n_kv) * D * 4);
   l.part_ml = p; p += align_up((size_t)b * n_kv * l.max_splits * (n_q / n_kv) * 2 * 4);
   l.dbg_page = p; p += align_up((size_t)UNIT_BYTES);
+  l.tstamp = p;  p += align_up((size_t)64 * 8);
   l.ctx_bytes = p;
   l.total = l.layer_bytes * c.n_layers + l.ctx_bytes;
   l.host_layer_bytes = c.placement == FKV_PLACE_HOST ? (size_t)b * n_kv * l.max_pages * UNIT_BYTES : 0;
@@ -142,11 +145,15 @@ struct fkv_ctx {
   uint8_t* flags(int l) const { return reinterpret_cast<uint8_t*>(layer_base(l) + lay.flags); }
   int32_t* miss(int l) const { return reinterpret_cast<int32_t*>(layer_base(l) + lay.miss); }
   double* cosine(int l) const { return reinterpret_cast<double*>(layer_base(l) + lay.cosine); }
+  int* sel_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters); }
+  int* attn_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + cfg.batch * cfg.n_kv_heads; }
   float* P() const { return reinterpret_cast<float*>(ctx_base() + lay.P); }
   float* score() const { return reinterpret_cast<float*>(ctx_base() + lay.score); }
   float* part_o() const { return reinterpret_cast<float*>(ctx_base() + lay.part_o); }
   float* part_ml() const { return reinterpret_cast<float*>(ctx_base() + lay.part_ml); }
   uint16_t* dbg_page() const { return reinterpret_cast<uint16_t*>(ctx_base() + lay.dbg_page); }
+  bool stamp_on = false;   // FKV_TSTAMP=1: kernels record phase timestamps of head 0 (debugging aid)
+  long long* tstamp() const { return stamp_on ? reinterpret_cast<long long*>(ctx_base() + lay.tstamp) : nullptr; }
 
   int fail(int code, const std::string& msg) { err = msg; return code; }
   int hip_fail(hipError_t e, const char* what) {
@@ -178,10 +185,66 @@ static int wait_recall(fkv_ctx* ctx, LayerState& ls, hipStream_t st) {
   return FKV_OK;
 }
 
+static const void* ctx_base_tstamp(const fkv_ctx* ctx) { return ctx->ctx_base() + ctx->lay.tstamp; }
+
 static int after_launch(fkv_ctx* ctx, const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return ctx->hip_fail(e, what);
   return FKV_OK;
+}
+
+// One launch of the step kernel with the given roles (append / correction test / selection).
+static int run_step(fkv_ctx* ctx, int layer, int roles, const void* q, const void* k_new, const void* v_new,
+                    uint8_t* flags_user, int32_t* ids_user, int L_after, hipStream_t st) {
+  LayerState& ls = ctx->layers[layer];
+  StepIO io{};
+  io.pd = ctx->pool_desc(layer);
+  io.summ = ctx->summ(layer);
+  io.k_new = static_cast<const uint16_t*>(k_new);
+  io.v_new = static_cast<const uint16_t*>(v_new);
+  io.q = static_cast<const uint16_t*>(q);
+  io.q_prev = ctx->qprev(layer, ls.parity ^ 1);
+  io.q_stage = ctx->qprev(layer, ls.parity);
+  io.have_prev = ls.have_prev_q ? 1 : 0;
+  io.tau = ctx->cfg.tau;
+  io.flags = ctx->flags(layer);
+  io.flags_user = flags_user;
+  io.cosine = ctx->cosine(layer);
+  io.P = ctx->P();
+  io.score = ctx->score();
+  io.ids = ctx->ids(layer, ls.parity);
+  io.ids_user = ids_user;
+  io.counters = ctx->sel_counters(layer);
+  io.tstamp = ctx->tstamp();
+  launch_step(ctx->dims, roles, io, make_geom(ctx->cfg, L_after), st);
+  return after_launch(ctx, "step kernel");
+}
+
+// Host-side bookkeeping after an append has been enqueued; placement HOST offloads a page
+// the token filled (Sec. 4.2), behind the append, on the copy stream.
+static int after_append(fkv_ctx* ctx, int layer, hipStream_t st, hipStream_t cs) {
+  LayerState& ls = ctx->layers[layer];
+  ls.L += 1;
+  if (ctx->cfg.placement == FKV_PLACE_HOST && ls.L % PG == 0) {
+    if (cs != st) {
+      FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+      FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
+    }
+    launch_offload(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ls.L / PG - 1, cs);
+    int rc = after_launch(ctx, "offload kernel");
+    if (rc) return rc;
+    FKV_HIP(ctx, hipEventRecord(ls.ev_offload, cs));
+    ls.offload_outstanding = true;
+  }
+  return FKV_OK;
+}
+
+static int run_plan(fkv_ctx* ctx, int layer, hipStream_t st) {
+  LayerState& ls = ctx->layers[layer];
+  if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
+  launch_plan(ctx->dims, ctx->ids(layer, ls.parity), ctx->ids(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity ^ 1),
+              ctx->slots(layer, ls.parity), ctx->miss(layer), st);
+  return after_launch(ctx, "plan kernel");
 }
 
 extern "C" {
@@ -211,10 +274,18 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   fkv_ctx* ctx = new fkv_ctx();
   ctx->cfg = *cfg;
   ctx->lay = l;
-  ctx->dims = Dims{cfg->batch, cfg->n_q_heads, cfg->n_kv_heads, cfg->n_q_heads / cfg->n_kv_heads, l.k, l.max_pages, cfg->dtype};
+  int dev_id = 0, max_lds = 65536;
+  if (hipGetDevice(&dev_id) == hipSuccess) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id) == hipSuccess && v > 0) max_lds = v;
+    v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeSharedMemPerBlockOptin, dev_id) == hipSuccess && v > max_lds) max_lds = v;
+  }
+  ctx->dims = Dims{cfg->batch, cfg->n_q_heads, cfg->n_kv_heads, cfg->n_q_heads / cfg->n_kv_heads, l.k, l.max_pages, cfg->dtype, max_lds};
   ctx->dev = static_cast<char*>(dev_arena);
   ctx->host = cfg->placement == FKV_PLACE_HOST ? static_cast<char*>(host_arena) : nullptr;
   ctx->layers.resize(cfg->n_layers);
+  { const char* e = getenv("FKV_TSTAMP"); ctx->stamp_on = e && e[0] == '1'; }
   hipError_t e = hipMemset(dev_arena, 0, l.total);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
@@ -288,26 +359,9 @@ int fkv_kv_append(fkv_ctx* ctx, int32_t layer, const void* k_new_dev, const void
   LayerState& ls = ctx->layers[layer];
   if (ls.L >= ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "append beyond max_ctx");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipStream_t cs = static_cast<hipStream_t>(copy_stream);
-  const Geom g = make_geom(ctx->cfg, ls.L + 1);
-  launch_append(ctx->dims, ctx->pool_desc(layer), ctx->summ(layer), static_cast<const uint16_t*>(k_new_dev),
-                static_cast<const uint16_t*>(v_new_dev), g, st);
-  int rc = after_launch(ctx, "append kernel");
+  int rc = run_step(ctx, layer, ROLE_APPEND, nullptr, k_new_dev, v_new_dev, nullptr, nullptr, ls.L + 1, st);
   if (rc) return rc;
-  ls.L += 1;
-  if (ctx->cfg.placement == FKV_PLACE_HOST && g.r == 0) {
-    // the token filled page n_full - 1: offload it (Sec. 4.2) behind the append, on the copy stream
-    if (cs != st) {
-      FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
-      FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
-    }
-    launch_offload(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), g.n_full - 1, cs);
-    rc = after_launch(ctx, "offload kernel");
-    if (rc) return rc;
-    FKV_HIP(ctx, hipEventRecord(ls.ev_offload, cs));
-    ls.offload_outstanding = true;
-  }
-  return FKV_OK;
+  return after_append(ctx, layer, st, static_cast<hipStream_t>(copy_stream));
 }
 
 int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int32_t n_pages, void* stream) {
@@ -325,12 +379,10 @@ int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flag
   FKV_CHECK_LAYER(ctx, layer);
   if (!q_dev) return ctx->fail(FKV_EINVAL, "null q");
   LayerState& ls = ctx->layers[layer];
-  int rcw = wait_recall(ctx, ls, static_cast<hipStream_t>(stream));
-  if (rcw) return rcw;
-  launch_corr(ctx->dims, static_cast<const uint16_t*>(q_dev), ctx->qprev(layer, ls.parity ^ 1),
-              ctx->qprev(layer, ls.parity), ls.have_prev_q ? 1 : 0, ctx->cfg.tau, ctx->flags(layer),
-              flags_dev, ctx->cosine(layer), static_cast<hipStream_t>(stream));
-  int rc = after_launch(ctx, "corr kernel");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = wait_recall(ctx, ls, st);
+  if (rc) return rc;
+  rc = run_step(ctx, layer, ROLE_CORR, q_dev, nullptr, nullptr, flags_dev, nullptr, ls.L, st);
   if (rc) return rc;
   ls.staged_q = true;
   ls.have_flags = true;
@@ -343,21 +395,12 @@ int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* pag
   LayerState& ls = ctx->layers[layer];
   if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const Geom g = make_geom(ctx->cfg, ls.L);
-  int rcw = wait_recall(ctx, ls, st);
-  if (rcw) return rcw;
-  launch_score(ctx->dims, ctx->summ(layer), static_cast<const uint16_t*>(q_dev), ctx->P(), g, st);
-  int rc = after_launch(ctx, "score kernel");
+  int rc = wait_recall(ctx, ls, st);
   if (rc) return rc;
-  launch_select(ctx->dims, ctx->P(), ctx->score(), ctx->ids(layer, ls.parity), page_ids_dev, g, st);
-  rc = after_launch(ctx, "select kernel");
+  rc = run_step(ctx, layer, ROLE_SELECT, q_dev, nullptr, nullptr, nullptr, page_ids_dev, ls.L, st);
   if (rc) return rc;
-  if (ctx->cfg.placement == FKV_PLACE_HOST) {
-    launch_plan(ctx->dims, ctx->ids(layer, ls.parity), ctx->ids(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity ^ 1),
-                ctx->slots(layer, ls.parity), ctx->miss(layer), st);
-    rc = after_launch(ctx, "plan kernel");
-    if (rc) return rc;
-  }
+  rc = run_plan(ctx, layer, st);
+  if (rc) return rc;
   ls.have_pending = true;
   return FKV_OK;
 }
@@ -397,7 +440,8 @@ int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float
   }
   launch_attn(ctx->dims, ctx->pool_desc(layer), static_cast<const uint16_t*>(q_dev), ctx->ids(layer, ls.parity ^ 1),
               ctx->ids(layer, ls.parity), ctx->slots(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity),
-              ctx->flags(layer), use, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, out_dev, g, st, e0, e1);
+              ctx->flags(layer), use, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, ctx->attn_counters(layer),
+              out_dev, g, st, e0, e1, ctx->tstamp());
   return after_launch(ctx, "attention kernels");
 }
 
@@ -421,34 +465,43 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   LayerState& ls = ctx->layers[layer];
   hipStream_t st = static_cast<hipStream_t>(compute_stream);
   hipStream_t cs = static_cast<hipStream_t>(copy_stream);
-  int rc = fkv_kv_append(ctx, layer, k_new_dev, v_new_dev, compute_stream, copy_stream);
+  if (ls.L >= ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "append beyond max_ctx");
+  int rc = wait_recall(ctx, ls, st);
   if (rc) return rc;
-  rc = fkv_corr_check(ctx, layer, q_dev, nullptr, compute_stream);
+  // append + correction test + selection for all heads: one launch
+  rc = run_step(ctx, layer, ROLE_APPEND | ROLE_CORR | ROLE_SELECT, q_dev, k_new_dev, v_new_dev, nullptr, nullptr,
+                ls.L + 1, st);
   if (rc) return rc;
-  rc = fkv_page_select(ctx, layer, q_dev, nullptr, compute_stream);
+  rc = after_append(ctx, layer, st, cs);
   if (rc) return rc;
+  rc = run_plan(ctx, layer, st);
+  if (rc) return rc;
+  ls.staged_q = ls.have_flags = ls.have_pending = true;
   const bool host_pool = ctx->cfg.placement == FKV_PLACE_HOST;
+  bool deferred = false;
   if (host_pool) {
+    // other heads: recall for the next step on the copy stream, off the critical path
+    // (Sec. 3.2).  It needs the plan just made and writes only slots that neither this
+    // step's attention nor the corrected heads' recall touch, so it may start right here.
+    if (cs != st) {
+      FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+      FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
+      rc = fkv_recall_pages(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
+      if (rc) return rc;
+      FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
+      deferred = true;     // the next step of this layer waits for it, not this step's attention
+    }
     // corrected heads: recall before this step's attention (Sec. 3.3)
     rc = fkv_recall_pages(ctx, layer, FKV_HEADS_FLAGGED, compute_stream);
     if (rc) return rc;
   }
   rc = fkv_sparse_decode_attn(ctx, layer, q_dev, out_dev, FKV_USE_BY_FLAG, compute_stream);
   if (rc) return rc;
-  if (host_pool) {
-    // other heads: recall for the next step, off the critical path (Sec. 3.2)
-    if (cs != st) {
-      // the copy stream needs the plan (made before attention) and must not start before the
-      // previous deferred recall of this layer has been consumed: both hold once the
-      // compute stream has passed the point recorded here
-      FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
-      FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
-    }
-    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
+  if (host_pool && cs == st) {
+    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_UNFLAGGED, compute_stream);
     if (rc) return rc;
-    FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
-    ls.recall_outstanding = true;
   }
+  ls.recall_outstanding = deferred;
   return fkv_commit(ctx, layer);
 }
 
@@ -481,6 +534,40 @@ int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches) {
   return FKV_OK;
 }
 
+int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, float* out_dev, int32_t reps,
+                     void* stream, double* total_ms, int32_t* launches) {
+  if (!ctx || !q_dev || !out_dev || !total_ms || !launches || reps < 1) return FKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int l = 0; l < ctx->cfg.n_layers; ++l)
+    if (ctx->layers[l].L < 1 || !ctx->layers[l].have_active) return ctx->fail(FKV_ESTATE, "every layer needs a context and an active selection");
+  hipEvent_t e0, e1;
+  FKV_HIP(ctx, hipEventCreate(&e0));
+  FKV_HIP(ctx, hipEventCreate(&e1));
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  FKV_HIP(ctx, hipEventRecord(e0, st));
+  int n = 0;
+  for (int r = 0; r < reps; ++r) {
+    for (int l = 0; l < ctx->cfg.n_layers; ++l, ++n) {
+      const LayerState& ls = ctx->layers[l];
+      launch_attn(ctx->dims, ctx->pool_desc(l), reinterpret_cast<const uint16_t*>(static_cast<const char*>(q_dev) + q_layer_stride * l),
+                  ctx->ids(l, ls.parity ^ 1), ctx->ids(l, ls.parity), ctx->slots(l, ls.parity ^ 1), ctx->slots(l, ls.parity),
+                  ctx->flags(l), FKV_USE_ACTIVE, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, ctx->attn_counters(l),
+                  out_dev, make_geom(ctx->cfg, ls.L), st, nullptr, nullptr, nullptr);
+    }
+  }
+  FKV_HIP(ctx, hipEventRecord(e1, st));
+  FKV_HIP(ctx, hipEventSynchronize(e1));
+  float ms = 0.f;
+  FKV_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  int rc = after_launch(ctx, "attention kernels");
+  if (rc) return rc;
+  *total_ms = ms;
+  *launches = n;
+  return FKV_OK;
+}
+
 int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes) {
   FKV_CHECK_LAYER(ctx, layer);
   if (!host_out) return ctx->fail(FKV_EINVAL, "null output");
@@ -497,6 +584,7 @@ int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, si
     case FKV_DBG_PENDING_IDS: src = ctx->ids(layer, ls.parity); n = (size_t)c.batch * c.n_kv_heads * kk * 4; break;
     case FKV_DBG_FLAGS:       src = ctx->flags(layer); n = (size_t)c.batch * c.n_kv_heads; break;
     case FKV_DBG_COSINE:      src = ctx->cosine(layer); n = (size_t)c.batch * c.n_q_heads * 8; break;
+    case FKV_DBG_TSTAMP:      src = ctx_base_tstamp(ctx); n = 64 * 8; break;
     case FKV_DBG_MISS: {
       n = (size_t)c.batch * c.n_kv_heads * (1 + kk) * 4;
       if (bytes < n) return ctx->fail(FKV_EINVAL, "output buffer too small");

@@ -1,5 +1,6 @@
 // Sparse decode attention over sink + picked pages + window + open page (Sec. 2.1),
-// split over pages with an online softmax, then a log-sum-exp merge.
+// split over pages with an online softmax; the block that finishes a KV head last does
+// the log-sum-exp merge of its splits.
 //
 // One wavefront owns one 32-token page at a time and keeps everything in registers:
 //   S^T[32 tok x 16] = K[32 x 128] . Q^T[128 x 16]       8 x v_mfma_f32_16x16x32
@@ -9,7 +10,7 @@
 // product holding the logits of head g for tokens {rb*4+i, 16+rb*4+i}: exactly the 8
 // tokens the same lane must supply as the B operand of the second product (the V page
 // is stored in that token order).  Nothing goes through LDS inside the page loop.
-#include "fkv_internal.h"
+#include "fkv_device.h"
 #include <cstdlib>
 
 namespace fkv {
@@ -56,6 +57,8 @@ template <> struct Mma<1> {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+constexpr int MAX_MERGE_SPLITS = 256;   // splits per KV head the fused merge can hold weights for
+
 // position i of a head's attend list -> HBM unit and number of valid tokens; -1 if the slot is empty
 struct AttendList {
   const int32_t* ids;     // picked page ids of this head (k entries, -1 padded)
@@ -90,9 +93,13 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16
                                                        const uint8_t* __restrict__ flags, int use,
                                                        float* __restrict__ part_o,
                                                        float* __restrict__ part_ml, int max_splits,
-                                                       int pps, Geom g, int n_q, int n_kv, int G, int k) {
+                                                       int pps, int n_splits, int* __restrict__ counters,
+                                                       float* __restrict__ out, Geom g, int n_q, int n_kv,
+                                                       int G, int k, long long* tstamp) {
   typedef typename Mma<DT>::vec vec;
   const int split = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
+#define FKV_ASTAMP(i) do { if (tstamp && m == 0 && b == 0 && threadIdx.x == 0) tstamp[i] = wall_clock64(); } while (0)
+  if (split == 0) FKV_ASTAMP(16);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int gq = lane & 15, rb = lane >> 4;
 
@@ -173,6 +180,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16
       acc[cb] = Mma<DT>::mma(va, plo, acc[cb]);
     }
   }
+  if (split == 0) FKV_ASTAMP(17);
   // per-wave totals of l over the 4 row blocks
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
@@ -182,9 +190,12 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16
   if (NW == 1) {
     if (gq < G) {
 #pragma unroll
-      for (int cb = 0; cb < 8; ++cb)
-        *reinterpret_cast<f32x4*>(po + (size_t)gq * D + cb * 16 + rb * 4) = acc[cb];
-      if (rb == 0) { pml[gq * 2] = m_run; pml[gq * 2 + 1] = l_run; }
+      for (int cb = 0; cb < 8; ++cb) {
+        float* dst = po + (size_t)gq * D + cb * 16 + rb * 4;
+        st_dev2(dst, acc[cb][0], acc[cb][1]);
+        st_dev2(dst + 2, acc[cb][2], acc[cb][3]);
+      }
+      if (rb == 0) st_dev2(pml + gq * 2, m_run, l_run);
     }
   } else {
     __shared__ float sm_m[NW][16];
@@ -204,51 +215,74 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16
       if (rb == 0) sm_l[wave][gq] = l_run * wgt;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < G * D; i += NW * 64) {
-      const int gg = i / D, c = i % D;
-      float s = 0.0f;
+    for (int i = threadIdx.x; i < G * D / 2; i += NW * 64) {
+      const int gg = i / (D / 2), c = (i % (D / 2)) * 2;
+      float s0 = 0.0f, s1 = 0.0f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) s += sm_o[w][gg][c];
-      po[(size_t)gg * D + c] = s;
+      for (int w = 0; w < NW; ++w) { s0 += sm_o[w][gg][c]; s1 += sm_o[w][gg][c + 1]; }
+      st_dev2(po + (size_t)gg * D + c, s0, s1);
     }
     if (threadIdx.x < G) {
       float s = 0.0f, MM = sm_m[0][threadIdx.x];
 #pragma unroll
       for (int w = 0; w < NW; ++w) { s += sm_l[w][threadIdx.x]; MM = fmaxf(MM, sm_m[w][threadIdx.x]); }
-      pml[threadIdx.x * 2] = MM;
-      pml[threadIdx.x * 2 + 1] = s;
+      st_dev2(pml + threadIdx.x * 2, MM, s);
     }
   }
-}
 
-// log-sum-exp merge of the splits: grid (n_q, batch), 128 threads = channels
-__global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ part_o,
-                                                    const float* __restrict__ part_ml, int max_splits,
-                                                    int n_splits, float* __restrict__ out, int n_q,
-                                                    int n_kv, int G) {
-  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  const int m = h / G, gg = h % G;
-  const size_t base = (size_t)(b * n_kv + m) * max_splits;
-  float M = -__builtin_inff();
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[((base + s) * G + gg) * 2]);
-  float num = 0.0f, den = 0.0f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float ms = part_ml[((base + s) * G + gg) * 2];
-    const float w = (ms == -__builtin_inff()) ? 0.0f : fast_exp2(ms - M);
-    den += w * part_ml[((base + s) * G + gg) * 2 + 1];
-    num += w * part_o[((base + s) * G + gg) * D + c];
+  // ---- log-sum-exp merge of this head's splits, by the block that finishes last ----
+  if (split == 0) FKV_ASTAMP(18);
+  if (!last_block_done(counters + b * n_kv + m, n_splits)) return;
+  FKV_ASTAMP(19);
+  // Every thread owns two output channels of one head and folds that head's splits with an
+  // online log-sum-exp.  The (m, l) pairs and the partial outputs of up to CH splits are all
+  // requested before the first one is used: one memory round trip per CH splits, no LDS.
+  const size_t pbase = (size_t)(b * n_kv + m) * max_splits;
+  const int nt = NW * 64, items = G * D / 2;
+  constexpr int CH = 32;
+  for (int it = threadIdx.x; it < items; it += nt) {
+    const int gg = it / (D / 2), c2 = it % (D / 2);
+    const float* src_o = part_o + (pbase * G + gg) * D + c2 * 2;
+    const float* src_ml = part_ml + (pbase * G + gg) * 2;
+    float M = -__builtin_inff(), den = 0.0f, o0 = 0.0f, o1 = 0.0f;
+    for (int s0 = 0; s0 < n_splits; s0 += CH) {
+      float2 ml[CH], v[CH];
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        const int sp = min(s0 + u, n_splits - 1);
+        ml[u] = ld_dev2(src_ml + (size_t)sp * G * 2);
+        v[u] = ld_dev2(src_o + (size_t)sp * G * D);
+      }
+      float Mc = M;
+#pragma unroll
+      for (int u = 0; u < CH; ++u)
+        if (s0 + u < n_splits) Mc = fmaxf(Mc, ml[u].x);
+      const float resc = (M == -__builtin_inff()) ? 0.0f : fast_exp2(M - Mc);
+      den *= resc; o0 *= resc; o1 *= resc;
+      M = Mc;
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        const float w = (s0 + u < n_splits && ml[u].x != -__builtin_inff()) ? fast_exp2(ml[u].x - M) : 0.0f;
+        den += w * ml[u].y;
+        o0 += w * v[u].x;
+        o1 += w * v[u].y;
+      }
+    }
+    const float inv = 1.0f / den;
+    *reinterpret_cast<float2*>(out + (size_t)(b * n_q + m * G + gg) * D + c2 * 2) = make_float2(o0 * inv, o1 * inv);
   }
-  out[(size_t)(b * n_q + h) * D + c] = num / den;
+  FKV_ASTAMP(21);
 }
 
 template <int DT>
 static void launch_attn_dt(int nw, dim3 grid, hipStream_t st, PoolDesc pd, const uint16_t* q,
                            const int32_t* act_ids, const int32_t* new_ids, const int32_t* act_slots,
                            const int32_t* new_slots, const uint8_t* flags, int use, float* part_o,
-                           float* part_ml, int max_splits, int pps, Geom g, const Dims& d) {
-  if (nw == 1)      attn_kernel<DT, 1><<<grid, 64, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d.n_q, d.n_kv, d.G, d.k);
-  else if (nw == 2) attn_kernel<DT, 2><<<grid, 128, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d.n_q, d.n_kv, d.G, d.k);
-  else              attn_kernel<DT, 4><<<grid, 256, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d.n_q, d.n_kv, d.G, d.k);
+                           float* part_ml, int max_splits, int pps, int n_splits, int* counters, float* out,
+                           Geom g, const Dims& d, long long* tstamp) {
+  if (nw == 1)      attn_kernel<DT, 1><<<grid, 64, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d.n_q, d.n_kv, d.G, d.k, tstamp);
+  else if (nw == 2) attn_kernel<DT, 2><<<grid, 128, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d.n_q, d.n_kv, d.G, d.k, tstamp);
+  else              attn_kernel<DT, 4><<<grid, 256, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d.n_q, d.n_kv, d.G, d.k, tstamp);
 }
 
 // tuning knob for experiments: pages per block (0 = choose from the shape)
@@ -257,23 +291,23 @@ static int g_pps_override = [] { const char* e = getenv("FKV_ATTN_PPS"); return 
 int launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
                 const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,
                 const uint8_t* flags, int use, float* part_o, float* part_ml, int max_splits,
-                float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
+                int* counters, float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end,
+                long long* tstamp) {
   const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
-  // pages per block: aim at >= ~2 blocks per compute unit, at most 4 waves per block
+  // 4 waves per block, a page per wave and pass; at most 32 splits per KV head so that the
+  // merge needs one round trip, unless that leaves most of the chip without a block
   const int heads = d.n_kv * d.batch;
-  int pps = 1;
-  while (pps < 16 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 256) pps *= 2;
+  int pps = 4;
+  while ((n_att + pps - 1) / pps > 32 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
+  while ((n_att + pps - 1) / pps > (max_splits < MAX_MERGE_SPLITS ? max_splits : MAX_MERGE_SPLITS)) pps *= 2;
   if (g_pps_override > 0) pps = g_pps_override;
-  while ((n_att + pps - 1) / pps > max_splits) pps *= 2;
   const int n_splits = (n_att + pps - 1) / pps;
   const int nw = pps >= 4 ? 4 : pps;
   dim3 grid(n_splits, d.n_kv, d.batch);
   if (ev_begin) (void)hipEventRecord(ev_begin, st);
-  if (d.dtype == 0) launch_attn_dt<0>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d);
-  else              launch_attn_dt<1>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, g, d);
+  if (d.dtype == 0) launch_attn_dt<0>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d, tstamp);
+  else              launch_attn_dt<1>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d, tstamp);
   if (ev_end) (void)hipEventRecord(ev_end, st);
-  dim3 mgrid(d.n_q, d.batch);
-  merge_kernel<<<mgrid, 128, 0, st>>>(part_o, part_ml, max_splits, n_splits, out, d.n_q, d.n_kv, d.G);
   return n_splits;
 }
 

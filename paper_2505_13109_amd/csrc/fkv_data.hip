@@ -1,52 +1,7 @@
-// Data-plane kernels: token append with incremental min-max summaries, bulk context
-// load, summary recompute, page offload to / recall from the host pool.
-#include "fkv_internal.h"
+// Data-plane kernels: bulk context load, summary recompute, page offload to / recall from the host pool.
+#include "fkv_device.h"
 
 namespace fkv {
-
-template <int DT> struct Cvt;
-template <> struct Cvt<0> {   // fp16
-  static __device__ __forceinline__ float f(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
-};
-template <> struct Cvt<1> {   // bf16
-  static __device__ __forceinline__ float f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-};
-
-__device__ __forceinline__ int resident_unit(const PoolDesc& pd, int page) {
-  if (pd.placement == 0) return page;
-  return page < pd.ring_base ? page : pd.ring_base + page % pd.n_ring;
-}
-__device__ __forceinline__ size_t head_base(const PoolDesc& pd, int b, int m, int n_kv) {
-  return (size_t)(b * n_kv + m) * pd.units_per_head;
-}
-__device__ __forceinline__ size_t summ_idx(int b, int m, int n_kv, int which, int max_pages, int page) {
-  return ((size_t)((b * n_kv + m) * 2 + which) * max_pages + page) * D;
-}
-
-// ---- append one token: grid (n_kv, batch), 128 threads = channels -------------
-template <int DT>
-__global__ __launch_bounds__(128) void append_kernel(PoolDesc pd, uint16_t* __restrict__ summ,
-                                                     const uint16_t* __restrict__ k_new,
-                                                     const uint16_t* __restrict__ v_new, Geom g,
-                                                     int n_kv, int max_pages) {
-  const int m = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  const int pos = g.L - 1, page = pos / PG, t = pos % PG;
-  const uint16_t kb = k_new[(size_t)(b * n_kv + m) * D + c];
-  const uint16_t vb = v_new[(size_t)(b * n_kv + m) * D + c];
-  uint16_t* unit = pd.pool + (head_base(pd, b, m, n_kv) + resident_unit(pd, page)) * UNIT_ELEMS;
-  unit[k_elem_off(t, c)] = kb;
-  unit[v_elem_off(t, c)] = vb;
-  uint16_t* pmax = summ + summ_idx(b, m, n_kv, 0, max_pages, page) + c;
-  uint16_t* pmin = summ + summ_idx(b, m, n_kv, 1, max_pages, page) + c;
-  if (t == 0) {
-    *pmax = kb;
-    *pmin = kb;
-  } else {
-    const float kf = Cvt<DT>::f(kb);
-    if (kf > Cvt<DT>::f(*pmax)) *pmax = kb;
-    if (kf < Cvt<DT>::f(*pmin)) *pmin = kb;
-  }
-}
 
 // ---- bulk load: grid (n_pages, n_kv, batch), 256 threads ------------------------
 template <int DT>
@@ -104,10 +59,10 @@ __global__ __launch_bounds__(256) void load_prefix_kernel(PoolDesc pd, uint16_t*
   }
   if (tid < D) {
     uint16_t bmax = sk[tid], bmin = sk[tid];
-    float fmax_ = Cvt<DT>::f(bmax), fmin_ = fmax_;
+    float fmax_ = Unpack<DT>::one(bmax), fmin_ = fmax_;
     for (int t = 1; t < nv; ++t) {
       const uint16_t kb = sk[t * D + tid];
-      const float kf = Cvt<DT>::f(kb);
+      const float kf = Unpack<DT>::one(kb);
       if (kf > fmax_) { fmax_ = kf; bmax = kb; }
       if (kf < fmin_) { fmin_ = kf; bmin = kb; }
     }
@@ -126,10 +81,10 @@ __global__ __launch_bounds__(128) void summary_recompute_kernel(PoolDesc pd, uin
   if (nv == 0) return;
   const uint16_t* unit = pd.pool + (head_base(pd, b, m, n_kv) + page) * UNIT_ELEMS;
   uint16_t bmax = unit[k_elem_off(0, c)], bmin = bmax;
-  float fmax_ = Cvt<DT>::f(bmax), fmin_ = fmax_;
+  float fmax_ = Unpack<DT>::one(bmax), fmin_ = fmax_;
   for (int t = 1; t < nv; ++t) {
     const uint16_t kb = unit[k_elem_off(t, c)];
-    const float kf = Cvt<DT>::f(kb);
+    const float kf = Unpack<DT>::one(kb);
     if (kf > fmax_) { fmax_ = kf; bmax = kb; }
     if (kf < fmin_) { fmin_ = kf; bmin = kb; }
   }
@@ -239,13 +194,6 @@ __global__ __launch_bounds__(256) void read_page_kernel(const uint16_t* __restri
 }
 
 // ---- launch wrappers ----------------------------------------------------------------
-void launch_append(const Dims& d, const PoolDesc& pd, uint16_t* summ, const uint16_t* k_new,
-                   const uint16_t* v_new, Geom g, hipStream_t st) {
-  dim3 grid(d.n_kv, d.batch);
-  if (d.dtype == 0) append_kernel<0><<<grid, 128, 0, st>>>(pd, summ, k_new, v_new, g, d.n_kv, d.max_pages);
-  else              append_kernel<1><<<grid, 128, 0, st>>>(pd, summ, k_new, v_new, g, d.n_kv, d.max_pages);
-}
-
 void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint16_t* host_pool,
                         const uint16_t* K, const uint16_t* V, int n_tokens, Geom g, hipStream_t st) {
   (void)g;

@@ -51,21 +51,23 @@ __host__ __device__ inline int v_elem_off(int t, int ch) {
 }
 
 // ---- launch wrappers (defined in the kernel files) ----------------------
-struct Dims { int batch, n_q, n_kv, G, k, max_pages, dtype; };
+struct Dims { int batch, n_q, n_kv, G, k, max_pages, dtype, max_lds; };
 
-void launch_append(const Dims& d, const PoolDesc& pd, uint16_t* summ, const uint16_t* k_new,
-                   const uint16_t* v_new, Geom g, hipStream_t st);
+// the fused step kernel: roles are OR-ed
+constexpr int ROLE_APPEND = 1, ROLE_CORR = 2, ROLE_SELECT = 4;
+struct StepIO {
+  PoolDesc pd; uint16_t* summ; const uint16_t* k_new; const uint16_t* v_new;      // append
+  const uint16_t* q; const uint16_t* q_prev; uint16_t* q_stage; int have_prev; float tau;
+  uint8_t* flags; uint8_t* flags_user; double* cosine;                               // correction test
+  float* P; float* score; int32_t* ids; int32_t* ids_user; int* counters;            // selection
+  long long* tstamp;                                                                 // debug timestamps or null
+};
+void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st);
 void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint16_t* host_pool,
                         const uint16_t* K, const uint16_t* V, int n_tokens, Geom g, hipStream_t st);
 void launch_summary_recompute(const Dims& d, const PoolDesc& pd, uint16_t* summ, int first_page,
                               int n_pages, Geom g, hipStream_t st);
 void launch_offload(const Dims& d, const PoolDesc& pd, uint16_t* host_pool, int page, hipStream_t st);
-void launch_corr(const Dims& d, const uint16_t* q, const uint16_t* q_prev, uint16_t* q_stage,
-                 int have_prev, float tau, uint8_t* flags, uint8_t* flags_user, double* cosine,
-                 hipStream_t st);
-void launch_score(const Dims& d, const uint16_t* summ, const uint16_t* q, float* P, Geom g, hipStream_t st);
-void launch_select(const Dims& d, const float* P, float* score, int32_t* ids, int32_t* ids_user,
-                   Geom g, hipStream_t st);
 void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
                  int32_t* new_slots, int32_t* miss, hipStream_t st);
 void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
@@ -74,7 +76,8 @@ void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool,
 int  launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
                  const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,
                  const uint8_t* flags, int use, float* part_o, float* part_ml, int max_splits,
-                 float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
+                 int* counters, float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end,
+                 long long* tstamp);
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st);
 
 }  // namespace fkv

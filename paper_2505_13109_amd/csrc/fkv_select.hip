@@ -1,4 +1,8 @@
-// Correction test, page weights, softmax -> group-mean pooling and top-k.
+// The "step" kernel: token append + incremental summaries, correction test, page weights,
+// and (by the last scoring block of each KV head) softmax -> group-mean pooling -> top-k.
+// One launch; blocks take roles by index, because the three jobs do not depend on each
+// other inside a step: the page being appended to is never a candidate, and a page that
+// becomes a candidate had its summary completed at least a window ago.
 //
 // The selected page ids must be reproducible bit for bit, so the arithmetic that
 // decides them is restricted to IEEE fp32/fp64 operations in a fixed order
@@ -12,129 +16,153 @@
 //            0 below t < -64; E = rint(e * 2^31) as integer; Z = integer sum of E;
 //   pooling: fl32( (sum_g fp64(E_g) / fp64(Z_g), g ascending) / fp64(G) );
 //   top-k:   radix select on the fp32 bit pattern, ties to the lower page id.
-#include "fkv_internal.h"
+#include "fkv_device.h"
 
 #pragma clang fp contract(off)
 
 namespace fkv {
 
-template <int DT> struct Unpack;
-template <> struct Unpack<0> {   // fp16 pair in a 32-bit word
-  static __device__ __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu)); }
-  static __device__ __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+#define FKV_STAMP(a, head, i) do { if ((a).tstamp && (head) == 0 && threadIdx.x == 0) (a).tstamp[i] = wall_clock64(); } while (0)
+
+#ifndef FKV_STEP_THREADS
+#define FKV_STEP_THREADS 512
+#endif
+#ifndef FKV_SCORE_PASSES
+#define FKV_SCORE_PASSES 1
+#endif
+constexpr int STEP_THREADS = FKV_STEP_THREADS;         // >= 256 (the radix histograms have 256 bins)
+constexpr int STEP_WAVES = STEP_THREADS / 64;
+constexpr int SCORE_PASSES = FKV_SCORE_PASSES;
+constexpr int PAGES_PER_PASS = STEP_WAVES * 4;         // a wave scores 4 pages per pass
+constexpr int PAGES_PER_BLOCK = PAGES_PER_PASS * SCORE_PASSES;
+
+struct StepArgs {
+  int roles;                 // ROLE_* bits
+  int batch, n_q, n_kv, k, max_pages;
+  Geom g;                    // geometry with the appended token counted
+  // append
+  PoolDesc pd;
+  uint16_t* summ;
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  // correction test
+  const uint16_t* q;
+  const uint16_t* q_prev;
+  uint16_t* q_stage;
+  int have_prev;
+  float tau;
+  uint8_t* flags;
+  uint8_t* flags_user;
+  double* cosine;
+  // selection
+  float* P;
+  float* score;
+  int32_t* ids;
+  int32_t* ids_user;
+  int* counters;
+  int blocks_per_head;
+  int staged;                // the G x n_cand weights fit in LDS next to the keys
+  long long* tstamp;         // debug: 100 MHz timestamps of head 0's phases (may be null)
 };
-template <> struct Unpack<1> {   // bf16 pair
-  static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
-  static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-};
+
+// ---------------------------------------------------------------------------------
+// role: append one token (Sec. 3.2 summaries; Sec. 4.2 paged layout).  128 active threads.
+// ---------------------------------------------------------------------------------
 template <int DT>
-__device__ __forceinline__ void unpack8(const uint4& w, float* f) {
-  f[0] = Unpack<DT>::lo(w.x); f[1] = Unpack<DT>::hi(w.x);
-  f[2] = Unpack<DT>::lo(w.y); f[3] = Unpack<DT>::hi(w.y);
-  f[4] = Unpack<DT>::lo(w.z); f[5] = Unpack<DT>::hi(w.z);
-  f[6] = Unpack<DT>::lo(w.w); f[7] = Unpack<DT>::hi(w.w);
+__device__ __forceinline__ void append_role(const StepArgs& a, int head) {
+  const int c = threadIdx.x;
+  if (c >= D) return;   // 128 of the block's threads
+  const int b = head / a.n_kv, m = head % a.n_kv;
+  const int pos = a.g.L - 1, page = pos / PG, t = pos % PG;
+  const uint16_t kb = a.k_new[(size_t)head * D + c];
+  const uint16_t vb = a.v_new[(size_t)head * D + c];
+  uint16_t* pmax = a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, page) + c;
+  uint16_t* pmin = a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, page) + c;
+  uint16_t omax = kb, omin = kb;
+  if (t != 0) { omax = *pmax; omin = *pmin; }
+  uint16_t* unit = a.pd.pool + (head_base(a.pd, b, m, a.n_kv) + resident_unit(a.pd, page)) * UNIT_ELEMS;
+  unit[k_elem_off(t, c)] = kb;
+  unit[v_elem_off(t, c)] = vb;
+  const float kf = Unpack<DT>::one(kb);
+  if (t == 0 || kf > Unpack<DT>::one(omax)) *pmax = kb;
+  if (t == 0 || kf < Unpack<DT>::one(omin)) *pmin = kb;
 }
 
 // ---------------------------------------------------------------------------------
-// Correction test (Sec. 3.1, 3.3).  grid (n_kv, batch), 128 threads = channels.
+// role: correction test (Sec. 3.1, 3.3).  One wave per query head, fp64.
 // ---------------------------------------------------------------------------------
-template <int DT>
-__global__ __launch_bounds__(128) void corr_kernel(const uint16_t* __restrict__ q,
-                                                   const uint16_t* __restrict__ q_prev,
-                                                   uint16_t* __restrict__ q_stage, int have_prev,
-                                                   float tau, uint8_t* __restrict__ flags,
-                                                   uint8_t* __restrict__ flags_user,
-                                                   double* __restrict__ cosine, int n_q, int n_kv, int G) {
-  __shared__ double red[3][128];
-  __shared__ double cg[MAX_G];
-  const int m = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  for (int g = 0; g < G; ++g) {
-    const size_t idx = (size_t)(b * n_q + m * G + g) * D + c;
-    const uint16_t qb = q[idx];
-    double cosv = 0.0;
-    if (have_prev) {
-      const double a = (double)(DT == 0 ? Unpack<0>::lo(qb) : Unpack<1>::lo(qb));
-      const uint16_t pb = q_prev[idx];
-      const double p = (double)(DT == 0 ? Unpack<0>::lo(pb) : Unpack<1>::lo(pb));
-      red[0][c] = a * p;
-      red[1][c] = a * a;
-      red[2][c] = p * p;
-      __syncthreads();
-      for (int s = 64; s > 0; s >>= 1) {
-        if (c < s) {
-          red[0][c] += red[0][c + s];
-          red[1][c] += red[1][c + s];
-          red[2][c] += red[2][c + s];
-        }
-        __syncthreads();
-      }
-      if (c == 0) {
-        const double den = sqrt(red[1][0] * red[2][0]);
-        cosv = den > 0.0 ? red[0][0] / den : 0.0;
-        cg[g] = cosv;
-        cosine[b * n_q + m * G + g] = cosv;
-      }
-      __syncthreads();
-    } else if (c == 0) {
-      cosine[b * n_q + m * G + g] = 0.0;
-    }
-    q_stage[idx] = qb;
-  }
-  if (c == 0) {
-    uint8_t f = 1;
-    if (have_prev) {
-      double acc = 0.0;
-      for (int g = 0; g < G; ++g) acc = acc + cg[g];
-      f = (acc / (double)G) < (double)tau ? 1 : 0;
-    }
-    flags[b * n_kv + m] = f;
-    if (flags_user) flags_user[b * n_kv + m] = f;
-  }
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
 }
-
-// ---------------------------------------------------------------------------------
-// Page weights P^h_j from the min-max summaries (Sec. 3.2).
-// A 16-lane group owns one page: lane c8 holds channels 8*c8 .. 8*c8+7 of kmax and
-// kmin (one 16-byte load each, 1 KiB contiguous per wave and array), so a wave
-// scores 4 pages and a 256-thread block 16 pages per pass.
-// grid (ceil(n_cand / (16*PASSES)), n_kv, batch).
-// ---------------------------------------------------------------------------------
-constexpr int SCORE_PASSES = 1;
 
 template <int DT, int G>
-__global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ summ,
-                                                    const uint16_t* __restrict__ q,
-                                                    float* __restrict__ P, Geom g, int n_q, int n_kv,
-                                                    int max_pages) {
-  const int m = blockIdx.y, b = blockIdx.z;
+__device__ __forceinline__ void corr_role(const StepArgs& a, int head) {
+  __shared__ double cg[MAX_G];
+  const int b = head / a.n_kv, m = head % a.n_kv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int gg = wave; gg < G; gg += STEP_WAVES) {
+    const size_t idx = (size_t)(b * a.n_q + m * G + gg) * D + lane * 2;
+    const uint32_t qw = *reinterpret_cast<const uint32_t*>(a.q + idx);
+    double cosv = 0.0;
+    if (a.have_prev) {
+      const uint32_t pw = *reinterpret_cast<const uint32_t*>(a.q_prev + idx);
+      const double a0 = (double)Unpack<DT>::lo(qw), a1 = (double)Unpack<DT>::hi(qw);
+      const double p0 = (double)Unpack<DT>::lo(pw), p1 = (double)Unpack<DT>::hi(pw);
+      const double dot = wave_sum_f64(a0 * p0 + a1 * p1);
+      const double na = wave_sum_f64(a0 * a0 + a1 * a1);
+      const double nb = wave_sum_f64(p0 * p0 + p1 * p1);
+      const double den = sqrt(na * nb);
+      cosv = den > 0.0 ? dot / den : 0.0;
+    }
+    *reinterpret_cast<uint32_t*>(a.q_stage + idx) = qw;
+    if (lane == 0) {
+      cg[gg] = cosv;
+      a.cosine[b * a.n_q + m * G + gg] = cosv;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint8_t f = 1;
+    if (a.have_prev) {
+      double acc = 0.0;
+      for (int gg = 0; gg < G; ++gg) acc = acc + cg[gg];
+      f = (acc / (double)G) < (double)a.tau ? 1 : 0;
+    }
+    a.flags[head] = f;
+    if (a.flags_user) a.flags_user[head] = f;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// role: page weights P^h_j from the min-max summaries (Sec. 3.2).
+// A 16-lane group owns one page: lane c8 holds channels 8*c8 .. 8*c8+7 of kmax and
+// kmin (one 16-byte load each, 1 KiB contiguous per wave and array), so a wave
+// scores 4 pages and a block 16 pages.
+// ---------------------------------------------------------------------------------
+template <int DT, int G>
+__device__ __forceinline__ void score_role(const StepArgs& a, int head, int chunk) {
+  const int b = head / a.n_kv, m = head % a.n_kv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane >> 4, c8 = lane & 15;
-  const uint16_t* kmax = summ + ((size_t)((b * n_kv + m) * 2 + 0) * max_pages) * D;
-  const uint16_t* kmin = summ + ((size_t)((b * n_kv + m) * 2 + 1) * max_pages) * D;
-
-  // summaries first: their addresses do not depend on q
+  if (chunk * PAGES_PER_BLOCK >= a.g.n_cand) return;      // a block that only exists to run the selection
+  // all summary loads of the block's passes first, then q: everything is in flight at once
   uint4 wmax[SCORE_PASSES], wmin[SCORE_PASSES];
   int page[SCORE_PASSES];
 #pragma unroll
   for (int ps = 0; ps < SCORE_PASSES; ++ps) {
-    const int j = (blockIdx.x * SCORE_PASSES + ps) * 16 + wave * 4 + grp;
-    page[ps] = j < g.n_cand ? g.cand_lo + j : -1;
-    const int jj = j < g.n_cand ? g.cand_lo + j : g.cand_lo;
-    wmax[ps] = *reinterpret_cast<const uint4*>(kmax + (size_t)jj * D + c8 * 8);
-    wmin[ps] = *reinterpret_cast<const uint4*>(kmin + (size_t)jj * D + c8 * 8);
+    const int j = chunk * PAGES_PER_BLOCK + ps * PAGES_PER_PASS + wave * 4 + grp;
+    page[ps] = j < a.g.n_cand ? a.g.cand_lo + j : -1;
+    const int pg = a.g.cand_lo + (j < a.g.n_cand ? j : 0);
+    wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
+    wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
   }
-  // q split by sign: q+ multiplies kmax, q- multiplies kmin; one of the two products is zero
-  float qp[G][8], qn[G][8];
+  float f[G][8];
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) {
-    const uint4 w = *reinterpret_cast<const uint4*>(q + (size_t)(b * n_q + m * G + gg) * D + c8 * 8);
-    float f[8];
-    unpack8<DT>(w, f);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      qp[gg][c] = f[c] >= 0.0f ? f[c] : 0.0f;
-      qn[gg][c] = f[c] >= 0.0f ? 0.0f : f[c];
-    }
+    const uint4 wq = *reinterpret_cast<const uint4*>(a.q + (size_t)(b * a.n_q + m * G + gg) * D + c8 * 8);
+    unpack8<DT>(wq, f[gg]);
   }
   const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
 #pragma unroll
@@ -144,26 +172,25 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
     unpack8<DT>(wmin[ps], kn);
 #pragma unroll
     for (int gg = 0; gg < G; ++gg) {
-      // chunk sum, left to right; each fma adds one exact product (the other one is +-0)
+      // chunk sum, left to right.  The product q_c * (q_c >= 0 ? kmax_c : kmin_c) is exact in
+      // fp32, so the fma rounds once, exactly like "s + product".
       float s = 0.0f;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        s = __builtin_fmaf(qp[gg][c], kx[c], s);
-        s = __builtin_fmaf(qn[gg][c], kn[c], s);
-      }
-      // adjacent-pair tree over the 16 chunk sums
-      s = s + __shfl_xor(s, 1, 64);
-      s = s + __shfl_xor(s, 2, 64);
-      s = s + __shfl_xor(s, 4, 64);
-      s = s + __shfl_xor(s, 8, 64);
+      for (int c = 0; c < 8; ++c) s = __builtin_fmaf(f[gg][c], f[gg][c] >= 0.0f ? kx[c] : kn[c], s);
+      // adjacent-pair tree over the 16 chunk sums (xor 1, 2 in quads; the mirrors pair lanes
+      // that hold equal partial sums' complements, which is the same tree)
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0xB1, 0xf, 0xf, false));
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x4E, 0xf, 0xf, false));
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x141, 0xf, 0xf, false));
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x140, 0xf, 0xf, false));
       const float w = s * scale;
-      if (c8 == gg && page[ps] >= 0) P[(size_t)(b * n_q + m * G + gg) * max_pages + page[ps]] = w;
+      if (c8 == gg && page[ps] >= 0) st_dev(a.P + (size_t)(b * a.n_q + m * G + gg) * a.max_pages + page[ps], w);
     }
   }
 }
 
 // ---------------------------------------------------------------------------------
-// softmax -> group mean -> top-k.  One 512-thread block per (KV head, request).
+// softmax -> group mean -> top-k for one KV head, by one 256-thread block.
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t softmax_fixed(float p, float mx) {
   const float x = p - mx;
@@ -182,133 +209,194 @@ __device__ __forceinline__ uint32_t softmax_fixed(float p, float mx) {
   return (uint32_t)__builtin_rintf(e * 2147483648.0f);
 }
 
-constexpr int SEL_THREADS = 512;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
+template <int G, bool STAGED>
+__device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32_t* key) {
+  __shared__ float s_redf[STEP_WAVES][G];
+  __shared__ unsigned long long s_redz[STEP_WAVES][G];
+  __shared__ uint32_t hist[4][256];
+  __shared__ uint32_t s_scan[STEP_WAVES];
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v = fmaxf(v, __shfl_xor(v, s, 64));
-  return v;
-}
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
-}
-
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __restrict__ P,
-                                                             float* __restrict__ score_out,
-                                                             int32_t* __restrict__ ids,
-                                                             int32_t* __restrict__ ids_user, Geom g,
-                                                             int n_q, int n_kv, int G, int k,
-                                                             int max_pages) {
-  extern __shared__ uint32_t key[];                 // n_cand pooled scores as ordered bit patterns
-  __shared__ float s_max[MAX_G];
-  __shared__ unsigned long long s_z[MAX_G];
-  __shared__ float s_redf[SEL_WAVES];
-  __shared__ unsigned long long s_redz[SEL_WAVES];
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_prefix, s_remaining;
-  __shared__ uint32_t s_scan[SEL_WAVES];
-
-  const int m = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int b = head / a.n_kv, m = head % a.n_kv, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int n = g.n_cand, lo = g.cand_lo, kk = g.k_eff;
-  int32_t* out = ids + (size_t)(b * n_kv + m) * k;
-  int32_t* outu = ids_user ? ids_user + (size_t)(b * n_kv + m) * k : nullptr;
-  for (int i = kk + tid; i < k; i += SEL_THREADS) {
-    out[i] = -1;
-    if (outu) outu[i] = -1;
+  const int n = a.g.n_cand, lo = a.g.cand_lo, kk = a.g.k_eff, k = a.k;
+  int32_t* out = a.ids + (size_t)head * k;
+  int32_t* outu = a.ids_user ? a.ids_user + (size_t)head * k : nullptr;
+  // No global store is issued before the last barrier of this function: a barrier waits for
+  // the acknowledgement of every store the wave has in flight, a full trip to memory.
+  if (kk == 0) {
+    for (int i = tid; i < k; i += STEP_THREADS) {
+      out[i] = -1;
+      if (outu) outu[i] = -1;
+    }
+    return;
   }
-  if (kk == 0) return;
+  const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
+  uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
+  constexpr bool staged = STAGED;                      // else: re-read the weights from memory in each pass
+  long long tk[8];
+#define FKV_TK(i) do { if (a.tstamp) tk[i] = clock64(); } while (0)
+  FKV_TK(0);
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+    if (tid < 256) hist[p][tid] = 0;
 
-  // per-head maximum over the candidates
+  // stage the weights of this head's G query heads in LDS (one device-scope read each, 8 x G
+  // of them in flight per thread) and take the per-head maximum over the candidates
+  float mx[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) mx[gg] = -__builtin_inff();
+  for (int j0 = tid; j0 < n; j0 += 8 * STEP_THREADS) {
+    float v[8][G];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = min(j0 + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) v[u][gg] = ld_dev(Pm + (size_t)gg * a.max_pages + j);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u * STEP_THREADS;
+      if (j < n) {
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) {
+          if (staged) pw[gg * n + j] = __float_as_uint(v[u][gg]);
+          mx[gg] = fmaxf(mx[gg], v[u][gg]);
+        }
+      }
+    }
+  }
+#pragma unroll
   for (int gg = 0; gg < G; ++gg) {
-    const float* Ph = P + (size_t)(b * n_q + m * G + gg) * max_pages + lo;
-    float mx = -__builtin_inff();
-    for (int j = tid; j < n; j += SEL_THREADS) mx = fmaxf(mx, Ph[j]);
-    mx = wave_max(mx);
-    if (lane == 0) s_redf[wave] = mx;
-    __syncthreads();
-    if (tid == 0) {
-      float v = s_redf[0];
-      for (int w = 1; w < SEL_WAVES; ++w) v = fmaxf(v, s_redf[w]);
-      s_max[gg] = v;
-    }
-    __syncthreads();
+    const float w = wave_max_f32(mx[gg]);
+    if (lane == 0) s_redf[wave][gg] = w;
   }
-  // integer softmax denominators
+  __syncthreads();
+#pragma unroll
   for (int gg = 0; gg < G; ++gg) {
-    const float* Ph = P + (size_t)(b * n_q + m * G + gg) * max_pages + lo;
-    const float mx = s_max[gg];
-    unsigned long long z = 0;
-    for (int j = tid; j < n; j += SEL_THREADS) z += softmax_fixed(Ph[j], mx);
-    z = wave_sum_u64(z);
-    if (lane == 0) s_redz[wave] = z;
-    __syncthreads();
-    if (tid == 0) {
-      unsigned long long v = 0;
-      for (int w = 0; w < SEL_WAVES; ++w) v += s_redz[w];
-      s_z[gg] = v;
-    }
-    __syncthreads();
+    float v = s_redf[0][gg];
+#pragma unroll
+    for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_redf[w][gg]);
+    mx[gg] = v;
   }
-  // pooled score of each candidate
-  for (int j = tid; j < n; j += SEL_THREADS) {
-    double acc = 0.0;
-    for (int gg = 0; gg < G; ++gg) {
-      const float p = P[(size_t)(b * n_q + m * G + gg) * max_pages + lo + j];
-      acc = acc + (double)softmax_fixed(p, s_max[gg]) / (double)s_z[gg];
+  FKV_TK(1);
+  // fixed-point softmax numerators in place, integer denominators (a sum of integers: no order to fix)
+  unsigned long long z[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) z[gg] = 0;
+  for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {   // 4 x G independent chains per trip
+    float v[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg)
+        v[u][gg] = staged ? __uint_as_float(pw[gg * n + j]) : ld_dev(Pm + (size_t)gg * a.max_pages + j);
     }
-    const float sc = (float)(acc / (double)G);
-    key[j] = __float_as_uint(sc);                  // sc >= 0: bit patterns order like the values
-    score_out[(size_t)(b * n_kv + m) * max_pages + lo + j] = sc;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * STEP_THREADS;
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        const uint32_t e = softmax_fixed(v[u][gg], mx[gg]);
+        if (j < n) {
+          if (staged) pw[gg * n + j] = e;
+          z[gg] += e;
+        }
+      }
+    }
   }
-  if (tid == 0) { s_prefix = 0; s_remaining = (uint32_t)kk; }
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    const unsigned long long w = wave_sum_u48(z[gg]);   // z < 2^31 * ceil(n / threads) < 2^48
+    if (lane == 0) s_redz[wave][gg] = w;
+  }
+  __syncthreads();
+  double zd[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    unsigned long long v = 0;
+#pragma unroll
+    for (int w = 0; w < STEP_WAVES; ++w) v += s_redz[w][gg];
+    zd[gg] = (double)v;
+  }
+  FKV_TK(2);
+  // pooled score of each candidate (each thread reads back only what it wrote); the top
+  // byte of its key goes straight into the first histogram
+  for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {
+    uint32_t e[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg)
+        e[u][gg] = staged ? pw[gg * n + j] : softmax_fixed(ld_dev(Pm + (size_t)gg * a.max_pages + j), mx[gg]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * STEP_THREADS;
+      double acc = 0.0;
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) acc = acc + (double)e[u][gg] / zd[gg];
+      const float sc = (float)(acc / (double)G);
+      const uint32_t kj = __float_as_uint(sc);       // sc >= 0: bit patterns order like the values
+      if (j < n) {
+        key[j] = kj;
+        atomicAdd(&hist[3][kj >> 24], 1u);
+      }
+    }
+  }
   __syncthreads();
 
-  // radix select: the kk-th largest key, one byte at a time from the top
+  FKV_TK(3);
+  // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
+  // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
+  uint32_t prefix = 0, remaining = (uint32_t)kk;
+#pragma unroll
   for (int pass = 3; pass >= 0; --pass) {
-    for (int i = tid; i < 256; i += SEL_THREADS) hist[i] = 0;
-    __syncthreads();
-    const uint32_t prefix = s_prefix;
     const int shift = pass * 8;
-    for (int j = tid; j < n; j += SEL_THREADS) {
-      const uint32_t kj = key[j];
-      if (pass == 3 || (kj >> (shift + 8)) == prefix) atomicAdd(&hist[(kj >> shift) & 255u], 1u);
+    if (pass != 3) {
+      for (int j = tid; j < n; j += STEP_THREADS) {
+        const uint32_t kj = key[j];
+        if ((kj >> (shift + 8)) == prefix) atomicAdd(&hist[pass][(kj >> shift) & 255u], 1u);
+      }
+      __syncthreads();
     }
-    __syncthreads();
-    if (tid == 0) {
-      uint32_t rem = s_remaining;
-      int bin = 255;
-      while (hist[bin] < rem) { rem -= hist[bin]; --bin; }
-      s_remaining = rem;                            // how many to take inside `bin`
-      s_prefix = (prefix << 8) | (uint32_t)bin;
+    uint32_t c[4], tot = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { c[i] = hist[pass][255 - 4 * lane - i]; tot += c[i]; }
+    const uint32_t incl = wave_scan_u32(tot);
+    uint32_t above = incl - tot;                     // keys in bins above this lane's
+    const bool mine = above < remaining && remaining <= incl;   // exactly one lane
+    uint32_t need = remaining - above;
+    int found = 0;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      if (found == i && c[i] < need) { need -= c[i]; found = i + 1; }
     }
-    __syncthreads();
+    const unsigned long long pick = __ballot(mine);
+    const int src = __builtin_ctzll(pick);
+    remaining = (uint32_t)__builtin_amdgcn_readlane((int)need, src);          // how many to take inside the bin
+    const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
+    prefix = (prefix << 8) | bin;
   }
-  const uint32_t T = s_prefix;                       // the kk-th largest key
-  const uint32_t take_eq = s_remaining;              // keys equal to T to take, lowest ids first
+  FKV_TK(4);
+  const uint32_t T = prefix;                         // the kk-th largest key
+  const uint32_t take_eq = remaining;                // keys equal to T to take, lowest ids first
 
   // ordered compaction: thread t owns the contiguous ids [t*per, (t+1)*per)
-  const int per = (n + SEL_THREADS - 1) / SEL_THREADS;
+  const int per = (n + STEP_THREADS - 1) / STEP_THREADS;
   const int j0 = tid * per, j1 = min(n, j0 + per);
   uint32_t cnt = 0;                                  // low 16 bits: keys > T, high 16 bits: keys == T
   for (int j = j0; j < j1; ++j) {
     const uint32_t kj = key[j];
     cnt += (kj > T ? 1u : 0u) + (kj == T ? 0x10000u : 0u);
   }
-  uint32_t incl = cnt;
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) {
-    const uint32_t v = __shfl_up(incl, s, 64);
-    if (lane >= s) incl += v;
-  }
+  const uint32_t incl = wave_scan_u32(cnt);
   if (lane == 63) s_scan[wave] = incl;
   __syncthreads();
   uint32_t base = 0;
   for (int w = 0; w < wave; ++w) base += s_scan[w];
-  uint32_t excl = base + incl - cnt;
+  const uint32_t excl = base + incl - cnt;
   uint32_t gt_before = excl & 0xffffu, eq_before = excl >> 16;
   for (int j = j0; j < j1; ++j) {
     const uint32_t kj = key[j];
@@ -320,40 +408,110 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     gt_before += (kj > T);
     eq_before += (kj == T);
   }
+  FKV_TK(5);
+  if (a.tstamp && head == 0 && tid == 0) for (int i = 0; i < 6; ++i) a.tstamp[40 + i] = tk[i];
+  for (int i = kk + tid; i < k; i += STEP_THREADS) {   // padding
+    out[i] = -1;
+    if (outu) outu[i] = -1;
+  }
+  for (int j = tid; j < n; j += STEP_THREADS)          // pooled scores, kept for inspection
+    a.score[(size_t)head * a.max_pages + lo + j] = __uint_as_float(key[j]);
 }
 
-// ---- launch wrappers ----------------------------------------------------------------
-void launch_corr(const Dims& d, const uint16_t* q, const uint16_t* q_prev, uint16_t* q_stage,
-                 int have_prev, float tau, uint8_t* flags, uint8_t* flags_user, double* cosine,
-                 hipStream_t st) {
-  dim3 grid(d.n_kv, d.batch);
-  if (d.dtype == 0) corr_kernel<0><<<grid, 128, 0, st>>>(q, q_prev, q_stage, have_prev, tau, flags, flags_user, cosine, d.n_q, d.n_kv, d.G);
-  else              corr_kernel<1><<<grid, 128, 0, st>>>(q, q_prev, q_stage, have_prev, tau, flags, flags_user, cosine, d.n_q, d.n_kv, d.G);
+// ---------------------------------------------------------------------------------
+// the kernel: 1-D grid, [append blocks][corr blocks][scoring blocks], each set present
+// only if its role bit is set; heads = batch * n_kv.
+// ---------------------------------------------------------------------------------
+template <int DT, int G>
+__global__ __launch_bounds__(STEP_THREADS) void step_kernel(StepArgs a) {
+  extern __shared__ uint32_t dyn_lds[];              // selection: n_cand keys, then G x n_cand weights
+  const int heads = a.batch * a.n_kv;
+  int bid = blockIdx.x;
+  if (a.roles & ROLE_APPEND) {
+    if (bid < heads) { append_role<DT>(a, bid); return; }
+    bid -= heads;
+  }
+  if (a.roles & ROLE_CORR) {
+    if (bid < heads) { corr_role<DT, G>(a, bid); return; }
+    bid -= heads;
+  }
+  const int head = bid / a.blocks_per_head, chunk = bid % a.blocks_per_head;
+  if (chunk == 0) FKV_STAMP(a, head, 0);
+  score_role<DT, G>(a, head, chunk);
+  if (chunk == 0) FKV_STAMP(a, head, 1);
+  if (!last_block_done(a.counters + head, a.blocks_per_head)) return;
+  FKV_STAMP(a, head, 2);
+  if (a.tstamp && head == 0 && threadIdx.x == 0) a.tstamp[30] = clock64();
+  if (a.staged) select_block<G, true>(a, head, dyn_lds);
+  else          select_block<G, false>(a, head, dyn_lds);
+  FKV_STAMP(a, head, 8);
+  if (a.tstamp && head == 0 && threadIdx.x == 0) a.tstamp[31] = clock64();
+}
+
+// Dynamic LDS above the default 64 KiB per block has to be granted per kernel function.
+// Returns false if the device refuses (the caller then keeps only the keys in LDS).
+template <int DT, int G>
+static bool raise_lds(size_t lds) {
+  static size_t granted = 0;
+  if (lds <= granted) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(&step_kernel<DT, G>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  granted = lds;
+  return true;
+}
+
+template <int DT, int G>
+static void launch_step_g(StepArgs& a, int grid, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+  constexpr size_t kDefaultLimit = 64 * 1024 - 8 * 1024;   // minus this kernel's static LDS, rounded up
+  size_t lds = lds_staged;
+  a.staged = lds_staged > lds_keys ? 1 : 0;
+  if (a.staged && lds > kDefaultLimit && !raise_lds<DT, G>(lds)) {
+    lds = lds_keys;
+    a.staged = 0;
+  }
+  if (!a.staged && lds > kDefaultLimit) (void)raise_lds<DT, G>(lds);
+  step_kernel<DT, G><<<grid, STEP_THREADS, lds, st>>>(a);
 }
 
 template <int DT>
-static void launch_score_dt(const Dims& d, const uint16_t* summ, const uint16_t* q, float* P, Geom g, hipStream_t st) {
-  dim3 grid((g.n_cand + 16 * SCORE_PASSES - 1) / (16 * SCORE_PASSES), d.n_kv, d.batch);
-  switch (d.G) {
-#define FKV_CASE(GG) case GG: score_kernel<DT, GG><<<grid, 256, 0, st>>>(summ, q, P, g, d.n_q, d.n_kv, d.max_pages); break;
+static void launch_step_dt(StepArgs& a, int G, int grid, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+  switch (G) {
+#define FKV_CASE(GG) case GG: launch_step_g<DT, GG>(a, grid, lds_staged, lds_keys, st); break;
     FKV_CASE(1) FKV_CASE(2) FKV_CASE(3) FKV_CASE(4) FKV_CASE(5) FKV_CASE(6) FKV_CASE(7) FKV_CASE(8)
 #undef FKV_CASE
     default: break;
   }
 }
 
-void launch_score(const Dims& d, const uint16_t* summ, const uint16_t* q, float* P, Geom g, hipStream_t st) {
-  if (g.n_cand <= 0) return;
-  if (d.dtype == 0) launch_score_dt<0>(d, summ, q, P, g, st);
-  else              launch_score_dt<1>(d, summ, q, P, g, st);
-}
-
-void launch_select(const Dims& d, const float* P, float* score, int32_t* ids, int32_t* ids_user,
-                   Geom g, hipStream_t st) {
-  if (d.k == 0) return;
-  dim3 grid(d.n_kv, d.batch);
-  const size_t lds = (size_t)(g.n_cand > 0 ? g.n_cand : 1) * sizeof(uint32_t);
-  select_kernel<<<grid, SEL_THREADS, lds, st>>>(P, score, ids, ids_user, g, d.n_q, d.n_kv, d.G, d.k, d.max_pages);
+void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st) {
+  if (d.k == 0) roles &= ~ROLE_SELECT;
+  if (roles == 0) return;
+  StepArgs a{};
+  a.roles = roles;
+  a.batch = d.batch; a.n_q = d.n_q; a.n_kv = d.n_kv; a.k = d.k; a.max_pages = d.max_pages;
+  a.g = g;
+  a.pd = io.pd; a.summ = io.summ; a.k_new = io.k_new; a.v_new = io.v_new;
+  a.q = io.q; a.q_prev = io.q_prev; a.q_stage = io.q_stage; a.have_prev = io.have_prev; a.tau = io.tau;
+  a.flags = io.flags; a.flags_user = io.flags_user; a.cosine = io.cosine;
+  a.P = io.P; a.score = io.score; a.ids = io.ids; a.ids_user = io.ids_user; a.counters = io.counters; a.tstamp = io.tstamp;
+  const int heads = d.batch * d.n_kv;
+  a.blocks_per_head = g.n_cand > 0 ? (g.n_cand + PAGES_PER_BLOCK - 1) / PAGES_PER_BLOCK : 1;
+  int grid = 0;
+  size_t lds_staged = 0, lds_keys = 0;
+  if (roles & ROLE_APPEND) grid += heads;
+  if (roles & ROLE_CORR) grid += heads;
+  if (roles & ROLE_SELECT) {
+    grid += heads * a.blocks_per_head;
+    const size_t n = (size_t)(g.n_cand > 0 ? g.n_cand : 1);
+    lds_keys = n * sizeof(uint32_t);
+    lds_staged = n * (1 + d.G) * sizeof(uint32_t);
+    if (lds_staged + 8192 > (size_t)d.max_lds) lds_staged = lds_keys;   // cannot fit: do not even ask
+  }
+  if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, lds_staged, lds_keys, st);
+  else              launch_step_dt<1>(a, d.G, grid, lds_staged, lds_keys, st);
 }
 
 }  // namespace fkv
