@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the split attention kernel at this workload, from
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs scaled by a copy kernel of known
 # size (profiles/attn_kernel_c2_pmc.txt).  None until measured.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = 9331500
 
 
 def algorithmic_bytes(wl):
@@ -97,8 +97,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c2", help="c2 is the benchmark workload; the others are for the design notes")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (stated in config.workload)")
+    ap.add_argument("--placement", type=int, default=-1, help="override KV placement: 0 HBM, 1 pinned host pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first run a plain elementwise kernel of known size (reads and writes 256 MiB) three "
+                         "times: the yardstick for HBM byte counters collected over this command")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards over KV heads / requests "
@@ -110,12 +115,22 @@ def main():
     import workloads as W
 
     wl = W.get_workload(args.workload)
+    if args.layers > 0:
+        wl = wl.scaled(n_layers=args.layers)
+    if args.placement >= 0:
+        wl = wl.scaled(placement=args.placement)
+    if args.calibration_copy:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda:0")
+        for _ in range(3):
+            b = a + 1          # vectorized_elementwise_kernel: 256 MiB read, 256 MiB written
+        torch.cuda.synchronize()
+        del a, b
     K, Wm = args.steps, args.warmup
     n_steps = K + Wm
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     p = wl.page_size
-    max_ctx = ((wl.ctx + 2 * n_steps + p - 1) // p) * p       # the steps are run twice (timed, then with kernel timers)
+    max_ctx = ((wl.ctx + 2 * n_steps + 16 + p - 1) // p) * p   # the steps are run twice (timed, then with kernel timers)
     ctx = fkv.FreeKV(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                      max_ctx=max_ctx, budget=wl.budget, sink=wl.sink, window=wl.window, tau=wl.tau,
                      dtype=wl.dtype, placement=wl.placement)
@@ -155,6 +170,23 @@ def main():
     # duration plus the dispatch gap, the figure a kernel trace reports
     attn_ms, attn_n = ctx.profile_attn(q[n_steps - 1], out[0], max(1, K // 4), stream=stream)
 
+    extra = {}
+    if wl.placement == 1:
+        # page-cache misses of a few more (untimed) steps, read back per layer
+        from paper_2505_13109_amd import binding as B
+        n_probe = min(8, Wm)
+        miss = picked = 0
+        for t in range(n_probe):
+            for layer in range(wl.n_layers):
+                ctx.decode_step(layer, q[Wm + t, layer], k_new[Wm + t, layer], v_new[Wm + t, layer], out[layer],
+                                stream=stream, copy_stream=copy_stream)
+                m = ctx.debug_read(layer, B.DBG_MISS)
+                miss += int(m[..., 0].sum())
+                picked += wl.batch * wl.n_kv_heads * wl.k_pages
+        extra = {"page_miss_rate": miss / max(picked, 1),
+                 "recall_bytes_per_layer_step": miss / max(n_probe * wl.n_layers, 1) * 16384}
+        extra["recall_GBps_if_exposed"] = extra["recall_bytes_per_layer_step"] / (elapsed / (K * wl.n_layers)) / 1e9
+
     layer_steps = K * wl.n_layers
     score_b, attn_b = algorithmic_bytes(wl)
     attn_s = attn_ms / 1e3 / max(attn_n, 1)
@@ -178,7 +210,7 @@ def main():
                                f"KV {'in HBM' if wl.placement == 0 else 'in pinned host memory'}",
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
-                   "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9},
+                   "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9, **extra},
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (split sparse decode attention)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
