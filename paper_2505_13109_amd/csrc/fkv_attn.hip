@@ -129,17 +129,31 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16
 #pragma unroll
   for (int cb = 0; cb < 8; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
+  // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
   const int p_end = min(n_att, (split + 1) * pps);
-  for (int pos = split * pps + wave; pos < p_end; pos += NW) {
-    int n_valid;
-    const int unit = attend_unit(al, pd, pos, n_valid);
-    if (unit < 0) continue;
+  int pos = split * pps + wave, unit = -1, n_valid = PG;
+  while (pos < p_end && (unit = attend_unit(al, pd, pos, n_valid)) < 0) pos += NW;
+  uint4 kw[8], vw[8];
+  if (unit >= 0) {
     const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)unit * UNIT_ELEMS) + lane;
-    uint4 kw[8], vw[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) kw[j] = up[j * 64];
 #pragma unroll
     for (int j = 0; j < 8; ++j) vw[j] = up[(8 + j) * 64];
+  }
+  while (unit >= 0) {
+    // next page of this wave, if any
+    int npos = pos + NW, nunit = -1, nn_valid = PG;
+    while (npos < p_end && (nunit = attend_unit(al, pd, npos, nn_valid)) < 0) npos += NW;
+    uint4 kn[8], vn[8];
+    if (nunit >= 0) {
+      const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)nunit * UNIT_ELEMS) + lane;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) kn[j] = up[j * 64];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) vn[j] = up[(8 + j) * 64];
+    }
 
     f32x4 st[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
@@ -178,6 +192,11 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16
       const vec va = __builtin_bit_cast(vec, vw[cb]);
       acc[cb] = Mma<DT>::mma(va, phi, acc[cb]);
       acc[cb] = Mma<DT>::mma(va, plo, acc[cb]);
+    }
+    pos = npos; unit = nunit; n_valid = nn_valid;
+    if (nunit >= 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { kw[j] = kn[j]; vw[j] = vn[j]; }
     }
   }
   if (split == 0) FKV_ASTAMP(17);

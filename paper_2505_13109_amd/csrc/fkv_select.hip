@@ -62,6 +62,8 @@ struct StepArgs {
   int* counters;
   int blocks_per_head;
   int staged;                // the G x n_cand weights fit in LDS next to the keys
+  int fuse_select;           // the last scoring block of a head runs its selection (else: a second launch does)
+  int select_only;           // this launch: one block per head, selection only
   long long* tstamp;         // debug: 100 MHz timestamps of head 0's phases (may be null)
 };
 
@@ -427,6 +429,11 @@ __global__ __launch_bounds__(STEP_THREADS) void step_kernel(StepArgs a) {
   extern __shared__ uint32_t dyn_lds[];              // selection: n_cand keys, then G x n_cand weights
   const int heads = a.batch * a.n_kv;
   int bid = blockIdx.x;
+  if (a.select_only) {
+    if (a.staged) select_block<G, true>(a, bid, dyn_lds);
+    else          select_block<G, false>(a, bid, dyn_lds);
+    return;
+  }
   if (a.roles & ROLE_APPEND) {
     if (bid < heads) { append_role<DT>(a, bid); return; }
     bid -= heads;
@@ -439,6 +446,7 @@ __global__ __launch_bounds__(STEP_THREADS) void step_kernel(StepArgs a) {
   if (chunk == 0) FKV_STAMP(a, head, 0);
   score_role<DT, G>(a, head, chunk);
   if (chunk == 0) FKV_STAMP(a, head, 1);
+  if (!a.fuse_select) return;
   if (!last_block_done(a.counters + head, a.blocks_per_head)) return;
   FKV_STAMP(a, head, 2);
   if (a.tstamp && head == 0 && threadIdx.x == 0) a.tstamp[30] = clock64();
@@ -463,23 +471,36 @@ static bool raise_lds(size_t lds) {
   return true;
 }
 
+// The selection's LDS (keys + staged weights) is allocated for every block of a launch.  When
+// it is small the selection rides in the scoring launch (its last block per head runs it);
+// when it would limit how many scoring blocks fit a compute unit, scoring runs without it and
+// a second launch of one block per head selects.
+constexpr size_t kFuseLdsLimit = 40 * 1024;
+
 template <int DT, int G>
-static void launch_step_g(StepArgs& a, int grid, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+static void launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
   constexpr size_t kDefaultLimit = 64 * 1024 - 8 * 1024;   // minus this kernel's static LDS, rounded up
+  const bool select = (a.roles & ROLE_SELECT) != 0;
   size_t lds = lds_staged;
   a.staged = lds_staged > lds_keys ? 1 : 0;
-  if (a.staged && lds > kDefaultLimit && !raise_lds<DT, G>(lds)) {
+  if (select && a.staged && lds > kDefaultLimit && !raise_lds<DT, G>(lds)) {
     lds = lds_keys;
     a.staged = 0;
   }
-  if (!a.staged && lds > kDefaultLimit) (void)raise_lds<DT, G>(lds);
-  step_kernel<DT, G><<<grid, STEP_THREADS, lds, st>>>(a);
+  if (select && !a.staged && lds > kDefaultLimit) (void)raise_lds<DT, G>(lds);
+  a.fuse_select = (select && lds <= kFuseLdsLimit) ? 1 : 0;
+  a.select_only = 0;
+  step_kernel<DT, G><<<grid, STEP_THREADS, a.fuse_select ? lds : 0, st>>>(a);
+  if (select && !a.fuse_select) {
+    a.select_only = 1;
+    step_kernel<DT, G><<<heads, STEP_THREADS, lds, st>>>(a);
+  }
 }
 
 template <int DT>
-static void launch_step_dt(StepArgs& a, int G, int grid, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+static void launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
   switch (G) {
-#define FKV_CASE(GG) case GG: launch_step_g<DT, GG>(a, grid, lds_staged, lds_keys, st); break;
+#define FKV_CASE(GG) case GG: launch_step_g<DT, GG>(a, grid, heads, lds_staged, lds_keys, st); break;
     FKV_CASE(1) FKV_CASE(2) FKV_CASE(3) FKV_CASE(4) FKV_CASE(5) FKV_CASE(6) FKV_CASE(7) FKV_CASE(8)
 #undef FKV_CASE
     default: break;
@@ -489,6 +510,13 @@ static void launch_step_dt(StepArgs& a, int G, int grid, size_t lds_staged, size
 void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st) {
   if (d.k == 0) roles &= ~ROLE_SELECT;
   if (roles == 0) return;
+  // The roles of one launch run concurrently.  That is safe because the page being appended to
+  // is not a candidate -- except with an empty window, when the token that fills a page makes
+  // that very page a candidate in the same step: then the append gets a launch of its own first.
+  if ((roles & ROLE_APPEND) && (roles & ROLE_SELECT) && g.r == 0 && g.n_win == 0 && g.n_cand > 0) {
+    launch_step(d, ROLE_APPEND, io, g, st);
+    roles &= ~ROLE_APPEND;
+  }
   StepArgs a{};
   a.roles = roles;
   a.batch = d.batch; a.n_q = d.n_q; a.n_kv = d.n_kv; a.k = d.k; a.max_pages = d.max_pages;
@@ -510,8 +538,8 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
     lds_staged = n * (1 + d.G) * sizeof(uint32_t);
     if (lds_staged + 8192 > (size_t)d.max_lds) lds_staged = lds_keys;   // cannot fit: do not even ask
   }
-  if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, lds_staged, lds_keys, st);
-  else              launch_step_dt<1>(a, d.G, grid, lds_staged, lds_keys, st);
+  if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, heads, lds_staged, lds_keys, st);
+  else              launch_step_dt<1>(a, d.G, grid, heads, lds_staged, lds_keys, st);
 }
 
 }  // namespace fkv

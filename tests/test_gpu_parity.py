@@ -66,6 +66,25 @@ def test_groups_of_1_2_3_5_6_8():
         pr.close()
 
 
+def test_empty_window_no_sink_and_nothing_selectable():
+    """W = 0 (a page becomes a candidate the moment it fills), S = 0, and budget = S + W (k = 0)."""
+    for sink, window, budget in ((0, 0, 256), (64, 0, 256), (0, 64, 192), (64, 64, 128)):
+        wl = W.Workload("edge", 1, 2, 8, 2, "bf16", 1000, budget, sink, window, 0.85, 70, 0.85, 0.527, 31)
+        pr = _pair(wl, [0])
+        for t in range(wl.steps):
+            pr.step(0, t)
+        pr.close()
+
+
+def test_batch_of_three_in_hbm():
+    wl = W.Workload("b3", 2, 3, 16, 4, "fp16", 5000, 1024, 128, 256, 0.8, 20, 0.8, 0.6, 77)
+    pr = _pair(wl, [0, 1])
+    for t in range(wl.steps):
+        for li in range(2):
+            pr.step(li, t)
+    pr.close()
+
+
 def test_primitives_and_call_order():
     import paper_2505_13109_amd as fkv
     from paper_2505_13109_amd import binding as B
