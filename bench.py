@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per launch of the split attention kernel at this workload, from
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs scaled by a copy kernel of known
-# size (profiles/attn_kernel_c2_pmc.txt).  None until measured.
-MEASURED_TRAFFIC_BYTES = 9331500
+# size (profiles/layer_step_c2_pmc.txt).  None until measured.
+MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9384700, "layer_kernel": 13956300}
 
 
 def algorithmic_bytes(wl):
@@ -153,10 +153,15 @@ def main():
 
     run(0, Wm)
     torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_begin = time.perf_counter()
+    ev0.record(stream)                     # HIP events on the launch stream, around the timed region
     run(Wm, n_steps)
+    ev1.record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
+    region_ms = ev0.elapsed_time(ev1)
+    one_launch = ctx.step_launches(0) == 1
     assert torch.isfinite(out).all()
 
     # second pass over the same step inputs with a HIP event pair around every launch of the
@@ -189,8 +194,20 @@ def main():
 
     layer_steps = K * wl.n_layers
     score_b, attn_b = algorithmic_bytes(wl)
-    attn_s = attn_ms / 1e3 / max(attn_n, 1)
-    achieved = attn_b / attn_s / 1e9
+    if one_launch:
+        # the whole layer-step is ONE kernel (layer_kernel): the timed region is K x n_layers
+        # back-to-back launches of it, so the event time over the region divided by the launches
+        # is its average launch-to-launch duration
+        kernel = "layer_kernel (append + correction test + page weights + top-k + sparse attention, one launch)"
+        kern_b = score_b + attn_b
+        kern_s = region_ms / 1e3 / layer_steps
+        kern_n = layer_steps
+    else:
+        kernel = "attn_kernel (split sparse decode attention)"
+        kern_b = attn_b
+        kern_s = attn_ms / 1e3 / max(attn_n, 1)
+        kern_n = attn_n
+    achieved = kern_b / kern_s / 1e9
     res = {
         "metric": "retrieval-decode layer-steps/s at 32K ctx",
         "value": layer_steps / elapsed,
@@ -211,11 +228,13 @@ def main():
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
                    "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9, **extra},
-        "roofline": {"bound": "hbm", "kernel": "attn_kernel (split sparse decode attention)",
+        "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "algorithmic_bytes_per_launch": attn_b, "avg_launch_us": attn_s * 1e6,
-                     "launches_timed": attn_n,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES["layer_kernel" if one_launch else "attn_kernel"] if wl.name == "c2" else None,
+                     "algorithmic_bytes_per_launch": kern_b, "avg_launch_us": kern_s * 1e6,
+                     "launches_timed": kern_n,
+                     "standalone_attn_kernel_us": attn_ms / max(attn_n, 1) * 1e3,
                      "event_pair_per_launch_us": pair_ms / max(pair_n, 1) * 1e3},
     }
     ctx.close()

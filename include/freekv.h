@@ -97,6 +97,10 @@ const char* fkv_last_error(const fkv_ctx* ctx);
 /* Tokens currently cached for `layer` (host-side counter), or a negative code. */
 int fkv_context_len(const fkv_ctx* ctx, int32_t layer);
 
+/* Kernel launches the last fkv_decode_step of `layer` put on the compute stream: 1 when the
+ * whole layer-step ran as one launch (KV in HBM, selection small enough), more otherwise. */
+int fkv_step_launches(const fkv_ctx* ctx, int32_t layer);
+
 /* ---- data plane ------------------------------------------------------- */
 
 /* Bulk-load a context of n_tokens (replaces the layer's state): stores K/V in

@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn",
+    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_step_launches",
 )
 
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         "fkv_destroy": (C.c_int, [vp]),
         "fkv_last_error": (C.c_char_p, [vp]),
         "fkv_context_len": (C.c_int, [vp, i32]),
+        "fkv_step_launches": (C.c_int, [vp, i32]),
         "fkv_load_prefix": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_kv_append": (C.c_int, [vp, i32, vp, vp, vp, vp]),
         "fkv_page_summary_update": (C.c_int, [vp, i32, i32, i32, vp]),
@@ -149,6 +150,9 @@ class FreeKV:
     # -- entry points ---------------------------------------------------------
     def context_len(self, layer):
         return self.L.fkv_context_len(self._h, layer)
+
+    def step_launches(self, layer):
+        return self.L.fkv_step_launches(self._h, layer)
 
     def load_prefix(self, layer, K, V, stream=None):
         assert K.is_contiguous() and V.is_contiguous() and K.dtype == self.torch_dtype

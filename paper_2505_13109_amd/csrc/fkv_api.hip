@@ -25,6 +25,8 @@ struct LayerState {
   bool have_flags = false;
   bool offload_outstanding = false;
   bool recall_outstanding = false;
+  int epoch = 0;             // decode steps taken through the one-launch path (selection epochs)
+  int last_launches = 0;     // kernel launches of the last fkv_decode_step (compute stream)
   hipEvent_t ev_offload = nullptr;   // last page offload finished
   hipEvent_t ev_recall = nullptr;    // deferred recall into ACTIVE's slots finished
 };
@@ -60,7 +62,7 @@ Layout make_layout(const fkv_config& c) {
   l.flags = o;  o += align_up((size_t)b * n_kv);
   l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 2 * l.k) * 4);
   l.cosine = o; o += align_up((size_t)b * n_q * 8);
-  l.counters = o; o += align_up((size_t)2 * b * n_kv * 4);   // last-block counters: selection, attention
+  l.counters = o; o += align_up((size_t)(3 * b * n_kv + 1) * 4);   // last-block counters (selection, attention), selection epochs, status
   l.layer_bytes = o;
   size_t p = 0;
   l.P = p;       p += align_up((size_t)b * n_q * l.max_pages * 4);
@@ -147,6 +149,8 @@ struct fkv_ctx {
   double* cosine(int l) const { return reinterpret_cast<double*>(layer_base(l) + lay.cosine); }
   int* sel_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters); }
   int* attn_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + cfg.batch * cfg.n_kv_heads; }
+  int* sel_done(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + 2 * cfg.batch * cfg.n_kv_heads; }
+  int* status(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + 3 * cfg.batch * cfg.n_kv_heads; }
   float* P() const { return reinterpret_cast<float*>(ctx_base() + lay.P); }
   float* score() const { return reinterpret_cast<float*>(ctx_base() + lay.score); }
   float* part_o() const { return reinterpret_cast<float*>(ctx_base() + lay.part_o); }
@@ -194,8 +198,8 @@ static int after_launch(fkv_ctx* ctx, const char* what) {
 }
 
 // One launch of the step kernel with the given roles (append / correction test / selection).
-static int run_step(fkv_ctx* ctx, int layer, int roles, const void* q, const void* k_new, const void* v_new,
-                    uint8_t* flags_user, int32_t* ids_user, int L_after, hipStream_t st) {
+static StepIO make_step_io(fkv_ctx* ctx, int layer, const void* q, const void* k_new, const void* v_new,
+                           uint8_t* flags_user, int32_t* ids_user) {
   LayerState& ls = ctx->layers[layer];
   StepIO io{};
   io.pd = ctx->pool_desc(layer);
@@ -216,6 +220,12 @@ static int run_step(fkv_ctx* ctx, int layer, int roles, const void* q, const voi
   io.ids_user = ids_user;
   io.counters = ctx->sel_counters(layer);
   io.tstamp = ctx->tstamp();
+  return io;
+}
+
+static int run_step(fkv_ctx* ctx, int layer, int roles, const void* q, const void* k_new, const void* v_new,
+                    uint8_t* flags_user, int32_t* ids_user, int L_after, hipStream_t st) {
+  const StepIO io = make_step_io(ctx, layer, q, k_new, v_new, flags_user, ids_user);
   launch_step(ctx->dims, roles, io, make_geom(ctx->cfg, L_after), st);
   return after_launch(ctx, "step kernel");
 }
@@ -329,6 +339,12 @@ int fkv_destroy(fkv_ctx* ctx) {
 
 const char* fkv_last_error(const fkv_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 
+int fkv_step_launches(const fkv_ctx* ctx, int32_t layer) {
+  if (!ctx) return FKV_EINVAL;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return FKV_ERANGE;
+  return ctx->layers[layer].last_launches;
+}
+
 int fkv_context_len(const fkv_ctx* ctx, int32_t layer) {
   if (!ctx) return FKV_EINVAL;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return FKV_ERANGE;
@@ -349,7 +365,10 @@ int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* 
   // a fresh context: no previous query, nothing picked
   const size_t n = (size_t)2 * ctx->cfg.batch * ctx->cfg.n_kv_heads * (ctx->lay.k > 0 ? ctx->lay.k : 1) * 4;
   FKV_HIP(ctx, hipMemsetAsync(ctx->ids(layer, 0), 0xff, n, st));
-  ls = LayerState{n_tokens, 0, false, false, false, false, false, false, false, ls.ev_offload, ls.ev_recall};
+  ls.L = n_tokens;
+  ls.parity = 0;
+  ls.have_prev_q = ls.have_active = ls.have_pending = ls.staged_q = ls.have_flags = false;
+  ls.offload_outstanding = ls.recall_outstanding = false;
   return FKV_OK;
 }
 
@@ -468,6 +487,36 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   if (ls.L >= ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "append beyond max_ctx");
   int rc = wait_recall(ctx, ls, st);
   if (rc) return rc;
+  if (ctx->cfg.placement == FKV_PLACE_HBM) {
+    // everything in one launch when the shape allows it
+    const StepIO io = make_step_io(ctx, layer, q_dev, k_new_dev, v_new_dev, nullptr, nullptr);
+    LayerIO lio{};
+    lio.act_ids = ctx->ids(layer, ls.parity ^ 1);
+    lio.part_o = ctx->part_o();
+    lio.part_ml = ctx->part_ml();
+    lio.max_splits = ctx->lay.max_splits;
+    lio.attn_counters = ctx->attn_counters(layer);
+    lio.out = out_dev;
+    lio.sel_done = ctx->sel_done(layer);
+    lio.epoch = ls.epoch + 1;
+    lio.status = ctx->status(layer);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (ctx->prof_on && ctx->prof_used + 2 <= ctx->prof_ev.size()) {
+      e0 = ctx->prof_ev[ctx->prof_used];
+      e1 = ctx->prof_ev[ctx->prof_used + 1];
+      (void)hipEventRecord(e0, st);
+    }
+    if (launch_layer(ctx->dims, io, lio, make_geom(ctx->cfg, ls.L + 1), st)) {
+      if (e0) { (void)hipEventRecord(e1, st); ctx->prof_used += 2; }
+      rc = after_launch(ctx, "layer kernel");
+      if (rc) return rc;
+      ls.epoch += 1;
+      ls.last_launches = 1;
+      ls.L += 1;
+      ls.staged_q = ls.have_flags = ls.have_pending = true;
+      return fkv_commit(ctx, layer);
+    }
+  }
   // append + correction test + selection for all heads: one launch
   rc = run_step(ctx, layer, ROLE_APPEND | ROLE_CORR | ROLE_SELECT, q_dev, k_new_dev, v_new_dev, nullptr, nullptr,
                 ls.L + 1, st);
@@ -502,6 +551,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     if (rc) return rc;
   }
   ls.recall_outstanding = deferred;
+  ls.last_launches = host_pool ? 5 : 2;
   return fkv_commit(ctx, layer);
 }
 

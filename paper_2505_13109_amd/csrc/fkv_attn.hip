@@ -1,311 +1,29 @@
-// Sparse decode attention over sink + picked pages + window + open page (Sec. 2.1),
-// split over pages with an online softmax; the block that finishes a KV head last does
-// the log-sum-exp merge of its splits.
-//
-// One wavefront owns one 32-token page at a time and keeps everything in registers:
-//   S^T[32 tok x 16] = K[32 x 128] . Q^T[128 x 16]       8 x v_mfma_f32_16x16x32
-//   O^T[128 x 16]   += V^T[128 x 32 tok] . P^T[32 x 16]   8 (x2: P split hi + lo) MFMAs
-// The query group (G <= 8 heads, padded to the 16 columns of the tile) is the N
-// dimension of both products, so lane (g = lane % 16, rb = lane / 16) ends the first
-// product holding the logits of head g for tokens {rb*4+i, 16+rb*4+i}: exactly the 8
-// tokens the same lane must supply as the B operand of the second product (the V page
-// is stored in that token order).  Nothing goes through LDS inside the page loop.
-#include "fkv_device.h"
+// Stand-alone launch of sparse decode attention (device code in fkv_attn_dev.h).
+#include "fkv_attn_dev.h"
 #include <cstdlib>
 
 namespace fkv {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-template <int DT> struct Mma;
-template <> struct Mma<0> {
-  typedef f16x8 vec;
-  static __device__ __forceinline__ f32x4 mma(vec a, vec b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-  }
-  // p >= 0 split into two storage-type values whose sum carries ~22 bits of p
-  static __device__ __forceinline__ void split(const float* p, vec& hi, vec& lo) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const _Float16 h = (_Float16)p[e];
-      hi[e] = h;
-      lo[e] = (_Float16)(p[e] - (float)h);
-    }
-  }
-};
-template <> struct Mma<1> {
-  typedef bf16x8 vec;
-  static __device__ __forceinline__ f32x4 mma(vec a, vec b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-  }
-  static __device__ __forceinline__ uint16_t rne(float x) {
-    const uint32_t u = __float_as_uint(x);
-    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-  }
-  static __device__ __forceinline__ void split(const float* p, vec& hi, vec& lo) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint16_t h = rne(p[e]);
-      const float hf = __uint_as_float(((uint32_t)h) << 16);
-      hi[e] = __builtin_bit_cast(__bf16, h);
-      lo[e] = __builtin_bit_cast(__bf16, rne(p[e] - hf));
-    }
-  }
-};
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-constexpr int MAX_MERGE_SPLITS = 256;   // splits per KV head the fused merge can hold weights for
-
-// position i of a head's attend list -> HBM unit and number of valid tokens; -1 if the slot is empty
-struct AttendList {
-  const int32_t* ids;     // picked page ids of this head (k entries, -1 padded)
-  const int32_t* slots;   // their page-cache slots (placement HOST)
-  int n_sink, k, n_win, n_full, r;
-};
-__device__ __forceinline__ int attend_unit(const AttendList& al, const PoolDesc& pd, int i, int& n_valid) {
-  n_valid = PG;
-  if (i < al.n_sink) return i;
-  i -= al.n_sink;
-  if (i < al.k) {
-    const int id = al.ids[i];
-    if (id < 0) return -1;
-    return pd.placement == 0 ? id : pd.sel_base + al.slots[i];
-  }
-  i -= al.k;
-  int page;
-  if (i < al.n_win) page = al.n_full - al.n_win + i;
-  else { page = al.n_full; n_valid = al.r; }
-  if (pd.placement == 0) return page;
-  return page < pd.ring_base ? page : pd.ring_base + page % pd.n_ring;
-}
-
-// grid (n_splits, n_kv, batch); NW wavefronts per block; block `split` owns attend-list
-// positions [split*pps, (split+1)*pps), wave w takes w, w+NW, ...
+// grid (n_splits, n_kv, batch); NW wavefronts per block
 template <int DT, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_kernel(PoolDesc pd, const uint16_t* __restrict__ q,
-                                                       const int32_t* __restrict__ act_ids,
-                                                       const int32_t* __restrict__ new_ids,
-                                                       const int32_t* __restrict__ act_slots,
-                                                       const int32_t* __restrict__ new_slots,
-                                                       const uint8_t* __restrict__ flags, int use,
-                                                       float* __restrict__ part_o,
-                                                       float* __restrict__ part_ml, int max_splits,
-                                                       int pps, int n_splits, int* __restrict__ counters,
-                                                       float* __restrict__ out, Geom g, int n_q, int n_kv,
-                                                       int G, int k, long long* tstamp) {
-  typedef typename Mma<DT>::vec vec;
-  const int split = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
-#define FKV_ASTAMP(i) do { if (tstamp && m == 0 && b == 0 && threadIdx.x == 0) tstamp[i] = wall_clock64(); } while (0)
-  if (split == 0) FKV_ASTAMP(16);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int gq = lane & 15, rb = lane >> 4;
-
-  const bool pending = use == 1 || (use == 2 && flags[b * n_kv + m] != 0);
-  AttendList al;
-  al.ids = (pending ? new_ids : act_ids) + (size_t)(b * n_kv + m) * k;
-  al.slots = pd.placement == 0 ? nullptr : (pending ? new_slots : act_slots) + (size_t)(b * n_kv + m) * k;
-  al.n_sink = g.n_sink; al.k = k; al.n_win = g.n_win; al.n_full = g.n_full; al.r = g.r;
-  const int n_att = g.n_sink + k + g.n_win + (g.r > 0 ? 1 : 0);
-  const uint16_t* head_pool = pd.pool + (size_t)(b * n_kv + m) * pd.units_per_head * UNIT_ELEMS;
-
-  // Q^T operand: lane (g, kb) holds channels (s*4+kb)*8 .. +8 of head g for k-step s
-  vec qv[4];
-  {
-    const uint16_t* qh = q + (size_t)(b * n_q + m * G + (gq < G ? gq : 0)) * D;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      uint4 w = *reinterpret_cast<const uint4*>(qh + (s * 4 + rb) * 8);
-      if (gq >= G) w = make_uint4(0, 0, 0, 0);
-      qv[s] = __builtin_bit_cast(vec, w);
-    }
-  }
-  const float sl2 = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(d) * log2(e)
-
-  float m_run = -__builtin_inff(), l_run = 0.0f;
-  f32x4 acc[8];
-#pragma unroll
-  for (int cb = 0; cb < 8; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
-  // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
-  const int p_end = min(n_att, (split + 1) * pps);
-  int pos = split * pps + wave, unit = -1, n_valid = PG;
-  while (pos < p_end && (unit = attend_unit(al, pd, pos, n_valid)) < 0) pos += NW;
-  uint4 kw[8], vw[8];
-  if (unit >= 0) {
-    const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)unit * UNIT_ELEMS) + lane;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) kw[j] = up[j * 64];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) vw[j] = up[(8 + j) * 64];
-  }
-  while (unit >= 0) {
-    // next page of this wave, if any
-    int npos = pos + NW, nunit = -1, nn_valid = PG;
-    while (npos < p_end && (nunit = attend_unit(al, pd, npos, nn_valid)) < 0) npos += NW;
-    uint4 kn[8], vn[8];
-    if (nunit >= 0) {
-      const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)nunit * UNIT_ELEMS) + lane;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) kn[j] = up[j * 64];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) vn[j] = up[(8 + j) * 64];
-    }
-
-    f32x4 st[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-        st[mb] = Mma<DT>::mma(__builtin_bit_cast(vec, kw[s * 2 + mb]), qv[s], st[mb]);
-    }
-    // logits (base 2) of head gq for tokens mb*16 + rb*4 + i
-    float sc[8];
-    float mx = -__builtin_inff();
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int tok = (e >> 2) * 16 + rb * 4 + (e & 3);
-      sc[e] = tok < n_valid ? st[e >> 2][e & 3] * sl2 : -__builtin_inff();
-      mx = fmaxf(mx, sc[e]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = fast_exp2(m_run - m_new);
-    float p[8], psum = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      p[e] = fast_exp2(sc[e] - m_new);
-      psum += p[e];
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) acc[cb] *= alpha;
-    vec phi, plo;
-    Mma<DT>::split(p, phi, plo);
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-      const vec va = __builtin_bit_cast(vec, vw[cb]);
-      acc[cb] = Mma<DT>::mma(va, phi, acc[cb]);
-      acc[cb] = Mma<DT>::mma(va, plo, acc[cb]);
-    }
-    pos = npos; unit = nunit; n_valid = nn_valid;
-    if (nunit >= 0) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) { kw[j] = kn[j]; vw[j] = vn[j]; }
-    }
-  }
-  if (split == 0) FKV_ASTAMP(17);
-  // per-wave totals of l over the 4 row blocks
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
-
-  float* po = part_o + ((size_t)((b * n_kv + m) * max_splits + split) * G) * D;
-  float* pml = part_ml + ((size_t)((b * n_kv + m) * max_splits + split) * G) * 2;
-  if (NW == 1) {
-    if (gq < G) {
-#pragma unroll
-      for (int cb = 0; cb < 8; ++cb) {
-        float* dst = po + (size_t)gq * D + cb * 16 + rb * 4;
-        st_dev2(dst, acc[cb][0], acc[cb][1]);
-        st_dev2(dst + 2, acc[cb][2], acc[cb][3]);
-      }
-      if (rb == 0) st_dev2(pml + gq * 2, m_run, l_run);
-    }
-  } else {
-    __shared__ float sm_m[NW][16];
-    __shared__ float sm_l[NW][16];
-    __shared__ __attribute__((aligned(16))) float sm_o[NW][MAX_G][D];
-    if (rb == 0) sm_m[wave][gq] = m_run;
-    __syncthreads();
-    float M = sm_m[0][gq];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w][gq]);
-    // a wave that saw no page has m_run = -inf and zero sums; exp2(-inf - M) = 0 unless M is -inf too
-    const float wgt = (m_run == -__builtin_inff()) ? 0.0f : fast_exp2(m_run - M);
-    if (gq < G) {
-#pragma unroll
-      for (int cb = 0; cb < 8; ++cb)
-        *reinterpret_cast<f32x4*>(&sm_o[wave][gq][cb * 16 + rb * 4]) = acc[cb] * wgt;
-      if (rb == 0) sm_l[wave][gq] = l_run * wgt;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < G * D / 2; i += NW * 64) {
-      const int gg = i / (D / 2), c = (i % (D / 2)) * 2;
-      float s0 = 0.0f, s1 = 0.0f;
-#pragma unroll
-      for (int w = 0; w < NW; ++w) { s0 += sm_o[w][gg][c]; s1 += sm_o[w][gg][c + 1]; }
-      st_dev2(po + (size_t)gg * D + c, s0, s1);
-    }
-    if (threadIdx.x < G) {
-      float s = 0.0f, MM = sm_m[0][threadIdx.x];
-#pragma unroll
-      for (int w = 0; w < NW; ++w) { s += sm_l[w][threadIdx.x]; MM = fmaxf(MM, sm_m[w][threadIdx.x]); }
-      st_dev2(pml + threadIdx.x * 2, MM, s);
-    }
-  }
-
-  // ---- log-sum-exp merge of this head's splits, by the block that finishes last ----
-  if (split == 0) FKV_ASTAMP(18);
-  if (!last_block_done(counters + b * n_kv + m, n_splits)) return;
-  FKV_ASTAMP(19);
-  // Every thread owns two output channels of one head and folds that head's splits with an
-  // online log-sum-exp.  The (m, l) pairs and the partial outputs of up to CH splits are all
-  // requested before the first one is used: one memory round trip per CH splits, no LDS.
-  const size_t pbase = (size_t)(b * n_kv + m) * max_splits;
-  const int nt = NW * 64, items = G * D / 2;
-  constexpr int CH = 32;
-  for (int it = threadIdx.x; it < items; it += nt) {
-    const int gg = it / (D / 2), c2 = it % (D / 2);
-    const float* src_o = part_o + (pbase * G + gg) * D + c2 * 2;
-    const float* src_ml = part_ml + (pbase * G + gg) * 2;
-    float M = -__builtin_inff(), den = 0.0f, o0 = 0.0f, o1 = 0.0f;
-    for (int s0 = 0; s0 < n_splits; s0 += CH) {
-      float2 ml[CH], v[CH];
-#pragma unroll
-      for (int u = 0; u < CH; ++u) {
-        const int sp = min(s0 + u, n_splits - 1);
-        ml[u] = ld_dev2(src_ml + (size_t)sp * G * 2);
-        v[u] = ld_dev2(src_o + (size_t)sp * G * D);
-      }
-      float Mc = M;
-#pragma unroll
-      for (int u = 0; u < CH; ++u)
-        if (s0 + u < n_splits) Mc = fmaxf(Mc, ml[u].x);
-      const float resc = (M == -__builtin_inff()) ? 0.0f : fast_exp2(M - Mc);
-      den *= resc; o0 *= resc; o1 *= resc;
-      M = Mc;
-#pragma unroll
-      for (int u = 0; u < CH; ++u) {
-        const float w = (s0 + u < n_splits && ml[u].x != -__builtin_inff()) ? fast_exp2(ml[u].x - M) : 0.0f;
-        den += w * ml[u].y;
-        o0 += w * v[u].x;
-        o1 += w * v[u].y;
-      }
-    }
-    const float inv = 1.0f / den;
-    *reinterpret_cast<float2*>(out + (size_t)(b * n_q + m * G + gg) * D + c2 * 2) = make_float2(o0 * inv, o1 * inv);
-  }
-  FKV_ASTAMP(21);
-}
-
-template <int DT>
-static void launch_attn_dt(int nw, dim3 grid, hipStream_t st, PoolDesc pd, const uint16_t* q,
-                           const int32_t* act_ids, const int32_t* new_ids, const int32_t* act_slots,
-                           const int32_t* new_slots, const uint8_t* flags, int use, float* part_o,
-                           float* part_ml, int max_splits, int pps, int n_splits, int* counters, float* out,
-                           Geom g, const Dims& d, long long* tstamp) {
-  if (nw == 1)      attn_kernel<DT, 1><<<grid, 64, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d.n_q, d.n_kv, d.G, d.k, tstamp);
-  else if (nw == 2) attn_kernel<DT, 2><<<grid, 128, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d.n_q, d.n_kv, d.G, d.k, tstamp);
-  else              attn_kernel<DT, 4><<<grid, 256, 0, st>>>(pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d.n_q, d.n_kv, d.G, d.k, tstamp);
+__global__ __launch_bounds__(NW * 64) void attn_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) float lds[NW > 1 ? NW * (32 + MAX_G * D) : 1];
+  attn_block<DT, NW>(a, blockIdx.x, blockIdx.y, blockIdx.z, lds);
 }
 
 // tuning knob for experiments: pages per block (0 = choose from the shape)
 static int g_pps_override = [] { const char* e = getenv("FKV_ATTN_PPS"); return e ? atoi(e) : 0; }();
+
+// pages per block of NW waves for a head with n_att attended pages
+int attn_pages_per_block(int n_att, int heads, int max_splits, int nw) {
+  // a page per wave and pass; at most 32 splits per KV head so that the merge needs one round
+  // trip, unless that leaves most of the chip without a block
+  int pps = nw;
+  while ((n_att + pps - 1) / pps > 32 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
+  while ((n_att + pps - 1) / pps > (max_splits < MAX_MERGE_SPLITS ? max_splits : MAX_MERGE_SPLITS)) pps *= 2;
+  if (g_pps_override > 0) pps = g_pps_override;
+  return pps;
+}
 
 int launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
                 const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,
@@ -313,21 +31,27 @@ int launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int3
                 int* counters, float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end,
                 long long* tstamp) {
   const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
-  // 4 waves per block, a page per wave and pass; at most 32 splits per KV head so that the
-  // merge needs one round trip, unless that leaves most of the chip without a block
-  const int heads = d.n_kv * d.batch;
-  int pps = 4;
-  while ((n_att + pps - 1) / pps > 32 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
-  while ((n_att + pps - 1) / pps > (max_splits < MAX_MERGE_SPLITS ? max_splits : MAX_MERGE_SPLITS)) pps *= 2;
-  if (g_pps_override > 0) pps = g_pps_override;
-  const int n_splits = (n_att + pps - 1) / pps;
-  const int nw = pps >= 4 ? 4 : pps;
-  dim3 grid(n_splits, d.n_kv, d.batch);
+  AttnArgs a{};
+  a.pd = pd; a.q = q; a.act_ids = act_ids; a.new_ids = new_ids; a.act_slots = act_slots; a.new_slots = new_slots;
+  a.flags = flags; a.use = use; a.part_o = part_o; a.part_ml = part_ml; a.max_splits = max_splits;
+  a.pps = attn_pages_per_block(n_att, d.n_kv * d.batch, max_splits, 4);
+  a.n_splits = (n_att + a.pps - 1) / a.pps;
+  a.counters = counters; a.out = out; a.g = g; a.n_q = d.n_q; a.n_kv = d.n_kv; a.G = d.G; a.k = d.k;
+  a.tstamp = tstamp; a.fused = 0;
+  const int nw = a.pps >= 4 ? 4 : a.pps;
+  dim3 grid(a.n_splits, d.n_kv, d.batch);
   if (ev_begin) (void)hipEventRecord(ev_begin, st);
-  if (d.dtype == 0) launch_attn_dt<0>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d, tstamp);
-  else              launch_attn_dt<1>(nw, grid, st, pd, q, act_ids, new_ids, act_slots, new_slots, flags, use, part_o, part_ml, max_splits, pps, n_splits, counters, out, g, d, tstamp);
+  if (d.dtype == 0) {
+    if (nw == 1)      attn_kernel<0, 1><<<grid, 64, 0, st>>>(a);
+    else if (nw == 2) attn_kernel<0, 2><<<grid, 128, 0, st>>>(a);
+    else              attn_kernel<0, 4><<<grid, 256, 0, st>>>(a);
+  } else {
+    if (nw == 1)      attn_kernel<1, 1><<<grid, 64, 0, st>>>(a);
+    else if (nw == 2) attn_kernel<1, 2><<<grid, 128, 0, st>>>(a);
+    else              attn_kernel<1, 4><<<grid, 256, 0, st>>>(a);
+  }
   if (ev_end) (void)hipEventRecord(ev_end, st);
-  return n_splits;
+  return a.n_splits;
 }
 
 }  // namespace fkv

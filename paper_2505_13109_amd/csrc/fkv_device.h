@@ -35,6 +35,25 @@ __device__ __forceinline__ size_t summ_idx(int b, int m, int n_kv, int which, in
   return ((size_t)((b * n_kv + m) * 2 + which) * max_pages + page) * D;
 }
 
+// cosine of one query head against the previous step's query (Sec. 3.1); one wave, fp64
+template <int DT>
+__device__ __forceinline__ double head_cosine(const uint16_t* q, const uint16_t* q_prev, int lane, uint32_t* q_word) {
+  const uint32_t qw = *reinterpret_cast<const uint32_t*>(q + lane * 2);
+  const uint32_t pw = *reinterpret_cast<const uint32_t*>(q_prev + lane * 2);
+  if (q_word) *q_word = qw;
+  const double a0 = (double)Unpack<DT>::lo(qw), a1 = (double)Unpack<DT>::hi(qw);
+  const double p0 = (double)Unpack<DT>::lo(pw), p1 = (double)Unpack<DT>::hi(pw);
+  double dot = a0 * p0 + a1 * p1, na = a0 * a0 + a1 * a1, nb = p0 * p0 + p1 * p1;
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) {
+    dot += __shfl_xor(dot, s, 64);
+    na += __shfl_xor(na, s, 64);
+    nb += __shfl_xor(nb, s, 64);
+  }
+  const double den = sqrt(na * nb);
+  return den > 0.0 ? dot / den : 0.0;
+}
+
 // ---- wavefront reductions on the DPP cross-lane path (no LDS traffic) ------------------
 // xor-1, xor-2 inside quads, then half-row and row mirrors: every lane of a 16-lane row ends
 // with the row's result; two row broadcasts carry it on, lane 63 holds the wave's result.

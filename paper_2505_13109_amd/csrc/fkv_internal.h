@@ -63,6 +63,14 @@ struct StepIO {
   long long* tstamp;                                                                 // debug timestamps or null
 };
 void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st);
+// the whole layer-step (step roles + attention) in one launch; false if this shape or placement
+// has to take the separate launches
+struct LayerIO {
+  const int32_t* act_ids; float* part_o; float* part_ml; int max_splits; int* attn_counters; float* out;
+  int* sel_done; int epoch; int* status;
+};
+bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, hipStream_t st);
+int attn_pages_per_block(int n_att, int heads, int max_splits, int nw);
 void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint16_t* host_pool,
                         const uint16_t* K, const uint16_t* V, int n_tokens, Geom g, hipStream_t st);
 void launch_summary_recompute(const Dims& d, const PoolDesc& pd, uint16_t* summ, int first_page,

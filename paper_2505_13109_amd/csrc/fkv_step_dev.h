@@ -1,0 +1,452 @@
+// Device code of the "step" roles: token append + incremental summaries, correction test, page weights,
+// and (by the last scoring block of each KV head) softmax -> group-mean pooling -> top-k.
+// One launch; blocks take roles by index, because the three jobs do not depend on each
+// other inside a step: the page being appended to is never a candidate, and a page that
+// becomes a candidate had its summary completed at least a window ago.
+//
+// The selected page ids must be reproducible bit for bit, so the arithmetic that
+// decides them is restricted to IEEE fp32/fp64 operations in a fixed order
+// (this file is compiled with -ffp-contract=off; FMAs are written explicitly
+// and only where the product is exact, so fusing cannot change the result):
+//   weight:  128 exact products summed as 16 chunks of 8 consecutive channels,
+//            left to right, then an adjacent-pair tree over the 16 chunk sums
+//            (the xor-1,2,4,8 butterfly of a 16-lane group), times fl32(1/sqrt(128));
+//   softmax: x = P - max; t = x * fl32(log2 e); n = rint(t); f = t - n;
+//            degree-6 Horner in f with separate multiply and add; ldexp(., n);
+//            0 below t < -64; E = rint(e * 2^31) as integer; Z = integer sum of E;
+//   pooling: fl32( (sum_g fp64(E_g) / fp64(Z_g), g ascending) / fp64(G) );
+//   top-k:   radix select on the fp32 bit pattern, ties to the lower page id.
+#pragma once
+#include "fkv_device.h"
+
+#pragma clang fp contract(off)
+
+namespace fkv {
+
+#define FKV_STAMP(a, head, i) do { if ((a).tstamp && (head) == 0 && threadIdx.x == 0) (a).tstamp[i] = wall_clock64(); } while (0)
+
+#ifndef FKV_STEP_THREADS
+#define FKV_STEP_THREADS 512
+#endif
+#ifndef FKV_SCORE_PASSES
+#define FKV_SCORE_PASSES 1
+#endif
+constexpr int STEP_THREADS = FKV_STEP_THREADS;         // >= 256 (the radix histograms have 256 bins)
+constexpr int STEP_WAVES = STEP_THREADS / 64;
+constexpr int SCORE_PASSES = FKV_SCORE_PASSES;
+constexpr int PAGES_PER_PASS = STEP_WAVES * 4;         // a wave scores 4 pages per pass
+constexpr int PAGES_PER_BLOCK = PAGES_PER_PASS * SCORE_PASSES;
+
+struct StepArgs {
+  int roles;                 // ROLE_* bits
+  int batch, n_q, n_kv, k, max_pages;
+  Geom g;                    // geometry with the appended token counted
+  // append
+  PoolDesc pd;
+  uint16_t* summ;
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  // correction test
+  const uint16_t* q;
+  const uint16_t* q_prev;
+  uint16_t* q_stage;
+  int have_prev;
+  float tau;
+  uint8_t* flags;
+  uint8_t* flags_user;
+  double* cosine;
+  // selection
+  float* P;
+  float* score;
+  int32_t* ids;
+  int32_t* ids_user;
+  int* counters;
+  int blocks_per_head;
+  int staged;                // the G x n_cand weights fit in LDS next to the keys
+  int fuse_select;           // the last scoring block of a head runs its selection (else: a second launch does)
+  int select_only;           // this launch: one block per head, selection only
+  long long* tstamp;         // debug: 100 MHz timestamps of head 0's phases (may be null)
+  int* sel_done;             // if not null: [heads], set to `epoch` once a head's page ids are out
+  int epoch;
+};
+
+// ---------------------------------------------------------------------------------
+// role: append one token (Sec. 3.2 summaries; Sec. 4.2 paged layout).  128 active threads.
+// ---------------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ void append_role(const StepArgs& a, int head) {
+  const int c = threadIdx.x;
+  if (c >= D) return;   // 128 of the block's threads
+  const int b = head / a.n_kv, m = head % a.n_kv;
+  const int pos = a.g.L - 1, page = pos / PG, t = pos % PG;
+  const uint16_t kb = a.k_new[(size_t)head * D + c];
+  const uint16_t vb = a.v_new[(size_t)head * D + c];
+  uint16_t* pmax = a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, page) + c;
+  uint16_t* pmin = a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, page) + c;
+  uint16_t omax = kb, omin = kb;
+  if (t != 0) { omax = *pmax; omin = *pmin; }
+  uint16_t* unit = a.pd.pool + (head_base(a.pd, b, m, a.n_kv) + resident_unit(a.pd, page)) * UNIT_ELEMS;
+  unit[k_elem_off(t, c)] = kb;
+  unit[v_elem_off(t, c)] = vb;
+  const float kf = Unpack<DT>::one(kb);
+  if (t == 0 || kf > Unpack<DT>::one(omax)) *pmax = kb;
+  if (t == 0 || kf < Unpack<DT>::one(omin)) *pmin = kb;
+}
+
+// ---------------------------------------------------------------------------------
+// role: correction test (Sec. 3.1, 3.3).  One wave per query head, fp64.
+// ---------------------------------------------------------------------------------
+template <int DT, int G>
+__device__ __forceinline__ void corr_role(const StepArgs& a, int head) {
+  __shared__ double cg[MAX_G];
+  const int b = head / a.n_kv, m = head % a.n_kv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int gg = wave; gg < G; gg += STEP_WAVES) {
+    const size_t off = (size_t)(b * a.n_q + m * G + gg) * D;
+    double cosv = 0.0;
+    uint32_t qw;
+    if (a.have_prev) cosv = head_cosine<DT>(a.q + off, a.q_prev + off, lane, &qw);
+    else qw = *reinterpret_cast<const uint32_t*>(a.q + off + lane * 2);
+    *reinterpret_cast<uint32_t*>(a.q_stage + off + lane * 2) = qw;
+    if (lane == 0) {
+      cg[gg] = cosv;
+      a.cosine[b * a.n_q + m * G + gg] = cosv;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint8_t f = 1;
+    if (a.have_prev) {
+      double acc = 0.0;
+      for (int gg = 0; gg < G; ++gg) acc = acc + cg[gg];
+      f = (acc / (double)G) < (double)a.tau ? 1 : 0;
+    }
+    a.flags[head] = f;
+    if (a.flags_user) a.flags_user[head] = f;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// role: page weights P^h_j from the min-max summaries (Sec. 3.2).
+// A 16-lane group owns one page: lane c8 holds channels 8*c8 .. 8*c8+7 of kmax and
+// kmin (one 16-byte load each, 1 KiB contiguous per wave and array), so a wave
+// scores 4 pages and a block 16 pages.
+// ---------------------------------------------------------------------------------
+template <int DT, int G>
+__device__ __forceinline__ void score_role(const StepArgs& a, int head, int chunk) {
+  const int b = head / a.n_kv, m = head % a.n_kv;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int grp = lane >> 4, c8 = lane & 15;
+  if (chunk * PAGES_PER_BLOCK >= a.g.n_cand) return;      // a block that only exists to run the selection
+  // all summary loads of the block's passes first, then q: everything is in flight at once
+  uint4 wmax[SCORE_PASSES], wmin[SCORE_PASSES];
+  int page[SCORE_PASSES];
+#pragma unroll
+  for (int ps = 0; ps < SCORE_PASSES; ++ps) {
+    const int j = chunk * PAGES_PER_BLOCK + ps * PAGES_PER_PASS + wave * 4 + grp;
+    page[ps] = j < a.g.n_cand ? a.g.cand_lo + j : -1;
+    const int pg = a.g.cand_lo + (j < a.g.n_cand ? j : 0);
+    wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
+    wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
+  }
+  float f[G][8];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    const uint4 wq = *reinterpret_cast<const uint4*>(a.q + (size_t)(b * a.n_q + m * G + gg) * D + c8 * 8);
+    unpack8<DT>(wq, f[gg]);
+  }
+  const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
+#pragma unroll
+  for (int ps = 0; ps < SCORE_PASSES; ++ps) {
+    float kx[8], kn[8];
+    unpack8<DT>(wmax[ps], kx);
+    unpack8<DT>(wmin[ps], kn);
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) {
+      // chunk sum, left to right.  The product q_c * (q_c >= 0 ? kmax_c : kmin_c) is exact in
+      // fp32, so the fma rounds once, exactly like "s + product".
+      float s = 0.0f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) s = __builtin_fmaf(f[gg][c], f[gg][c] >= 0.0f ? kx[c] : kn[c], s);
+      // adjacent-pair tree over the 16 chunk sums (xor 1, 2 in quads; the mirrors pair lanes
+      // that hold equal partial sums' complements, which is the same tree)
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0xB1, 0xf, 0xf, false));
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x4E, 0xf, 0xf, false));
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x141, 0xf, 0xf, false));
+      s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x140, 0xf, 0xf, false));
+      const float w = s * scale;
+      if (c8 == gg && page[ps] >= 0) st_dev(a.P + (size_t)(b * a.n_q + m * G + gg) * a.max_pages + page[ps], w);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// softmax -> group mean -> top-k for one KV head, by one 256-thread block.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t softmax_fixed(float p, float mx) {
+  const float x = p - mx;
+  const float t = x * 0x1.715476p+0f;          // fl32(log2 e)
+  const float n = __builtin_rintf(t);
+  const float f = t - n;
+  float r = 0x1.430912p-13f;
+  r = r * f; r = r + 0x1.5d87fep-10f;
+  r = r * f; r = r + 0x1.3b2ab6p-7f;
+  r = r * f; r = r + 0x1.c6b08ep-5f;
+  r = r * f; r = r + 0x1.ebfbep-3f;
+  r = r * f; r = r + 0x1.62e43p-1f;
+  r = r * f; r = r + 1.0f;
+  float e = __builtin_ldexpf(r, (int)n);
+  if (t < -64.0f) e = 0.0f;
+  return (uint32_t)__builtin_rintf(e * 2147483648.0f);
+}
+
+template <int G, bool STAGED>
+__device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32_t* key) {
+  __shared__ float s_redf[STEP_WAVES][G];
+  __shared__ unsigned long long s_redz[STEP_WAVES][G];
+  __shared__ uint32_t hist[4][256];
+  __shared__ uint32_t s_scan[STEP_WAVES];
+
+  const int b = head / a.n_kv, m = head % a.n_kv, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n = a.g.n_cand, lo = a.g.cand_lo, kk = a.g.k_eff, k = a.k;
+  int32_t* out = a.ids + (size_t)head * k;
+  int32_t* outu = a.ids_user ? a.ids_user + (size_t)head * k : nullptr;
+  // No global store is issued before the last barrier of this function: a barrier waits for
+  // the acknowledgement of every store the wave has in flight, a full trip to memory.
+  if (kk == 0) {
+    for (int i = tid; i < k; i += STEP_THREADS) {
+      __hip_atomic_store(out + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (outu) outu[i] = -1;
+    }
+    return;
+  }
+  const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
+  uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
+  constexpr bool staged = STAGED;                      // else: re-read the weights from memory in each pass
+  long long tk[8];
+#define FKV_TK(i) do { if (a.tstamp) tk[i] = clock64(); } while (0)
+  FKV_TK(0);
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+    if (tid < 256) hist[p][tid] = 0;
+
+  // stage the weights of this head's G query heads in LDS (one device-scope read each, 8 x G
+  // of them in flight per thread) and take the per-head maximum over the candidates
+  float mx[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) mx[gg] = -__builtin_inff();
+  for (int j0 = tid; j0 < n; j0 += 8 * STEP_THREADS) {
+    float v[8][G];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = min(j0 + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) v[u][gg] = ld_dev(Pm + (size_t)gg * a.max_pages + j);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u * STEP_THREADS;
+      if (j < n) {
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) {
+          if (staged) pw[gg * n + j] = __float_as_uint(v[u][gg]);
+          mx[gg] = fmaxf(mx[gg], v[u][gg]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    const float w = wave_max_f32(mx[gg]);
+    if (lane == 0) s_redf[wave][gg] = w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    float v = s_redf[0][gg];
+#pragma unroll
+    for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_redf[w][gg]);
+    mx[gg] = v;
+  }
+  FKV_TK(1);
+  // fixed-point softmax numerators in place, integer denominators (a sum of integers: no order to fix)
+  unsigned long long z[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) z[gg] = 0;
+  for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {   // 4 x G independent chains per trip
+    float v[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg)
+        v[u][gg] = staged ? __uint_as_float(pw[gg * n + j]) : ld_dev(Pm + (size_t)gg * a.max_pages + j);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * STEP_THREADS;
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        const uint32_t e = softmax_fixed(v[u][gg], mx[gg]);
+        if (j < n) {
+          if (staged) pw[gg * n + j] = e;
+          z[gg] += e;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    const unsigned long long w = wave_sum_u48(z[gg]);   // z < 2^31 * ceil(n / threads) < 2^48
+    if (lane == 0) s_redz[wave][gg] = w;
+  }
+  __syncthreads();
+  double zd[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) {
+    unsigned long long v = 0;
+#pragma unroll
+    for (int w = 0; w < STEP_WAVES; ++w) v += s_redz[w][gg];
+    zd[gg] = (double)v;
+  }
+  FKV_TK(2);
+  // pooled score of each candidate (each thread reads back only what it wrote); the top
+  // byte of its key goes straight into the first histogram
+  for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {
+    uint32_t e[4][G];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg)
+        e[u][gg] = staged ? pw[gg * n + j] : softmax_fixed(ld_dev(Pm + (size_t)gg * a.max_pages + j), mx[gg]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * STEP_THREADS;
+      double acc = 0.0;
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) acc = acc + (double)e[u][gg] / zd[gg];
+      const float sc = (float)(acc / (double)G);
+      const uint32_t kj = __float_as_uint(sc);       // sc >= 0: bit patterns order like the values
+      if (j < n) {
+        key[j] = kj;
+        atomicAdd(&hist[3][kj >> 24], 1u);
+      }
+    }
+  }
+  __syncthreads();
+
+  FKV_TK(3);
+  // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
+  // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
+  uint32_t prefix = 0, remaining = (uint32_t)kk;
+#pragma unroll
+  for (int pass = 3; pass >= 0; --pass) {
+    const int shift = pass * 8;
+    if (pass != 3) {
+      for (int j = tid; j < n; j += STEP_THREADS) {
+        const uint32_t kj = key[j];
+        if ((kj >> (shift + 8)) == prefix) atomicAdd(&hist[pass][(kj >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+    }
+    uint32_t c[4], tot = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { c[i] = hist[pass][255 - 4 * lane - i]; tot += c[i]; }
+    const uint32_t incl = wave_scan_u32(tot);
+    uint32_t above = incl - tot;                     // keys in bins above this lane's
+    const bool mine = above < remaining && remaining <= incl;   // exactly one lane
+    uint32_t need = remaining - above;
+    int found = 0;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      if (found == i && c[i] < need) { need -= c[i]; found = i + 1; }
+    }
+    const unsigned long long pick = __ballot(mine);
+    const int src = __builtin_ctzll(pick);
+    remaining = (uint32_t)__builtin_amdgcn_readlane((int)need, src);          // how many to take inside the bin
+    const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
+    prefix = (prefix << 8) | bin;
+  }
+  FKV_TK(4);
+  const uint32_t T = prefix;                         // the kk-th largest key
+  const uint32_t take_eq = remaining;                // keys equal to T to take, lowest ids first
+
+  // ordered compaction: thread t owns the contiguous ids [t*per, (t+1)*per)
+  const int per = (n + STEP_THREADS - 1) / STEP_THREADS;
+  const int j0 = tid * per, j1 = min(n, j0 + per);
+  uint32_t cnt = 0;                                  // low 16 bits: keys > T, high 16 bits: keys == T
+  for (int j = j0; j < j1; ++j) {
+    const uint32_t kj = key[j];
+    cnt += (kj > T ? 1u : 0u) + (kj == T ? 0x10000u : 0u);
+  }
+  const uint32_t incl = wave_scan_u32(cnt);
+  if (lane == 63) s_scan[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += s_scan[w];
+  const uint32_t excl = base + incl - cnt;
+  uint32_t gt_before = excl & 0xffffu, eq_before = excl >> 16;
+  for (int j = j0; j < j1; ++j) {
+    const uint32_t kj = key[j];
+    if (kj > T || (kj == T && eq_before < take_eq)) {
+      const uint32_t pos = gt_before + min(eq_before, take_eq);
+      __hip_atomic_store(out + pos, lo + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (outu) outu[pos] = lo + j;
+    }
+    gt_before += (kj > T);
+    eq_before += (kj == T);
+  }
+  FKV_TK(5);
+  if (a.tstamp && head == 0 && tid == 0) for (int i = 0; i < 6; ++i) a.tstamp[40 + i] = tk[i];
+  for (int i = kk + tid; i < k; i += STEP_THREADS) {   // padding
+    __hip_atomic_store(out + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (outu) outu[i] = -1;
+  }
+  for (int j = tid; j < n; j += STEP_THREADS)          // pooled scores, kept for inspection
+    a.score[(size_t)head * a.max_pages + lo + j] = __uint_as_float(key[j]);
+}
+
+
+// ---------------------------------------------------------------------------------
+// role dispatch of one block: bid counts [append blocks][corr blocks][scoring blocks], each
+// set present only if its role bit is set; heads = batch * n_kv.
+// ---------------------------------------------------------------------------------
+template <int DT, int G>
+__device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t* dyn_lds) {
+  const int heads = a.batch * a.n_kv;
+  int head;
+  if (a.select_only) {
+    head = bid;
+  } else {
+    if (a.roles & ROLE_APPEND) {
+      if (bid < heads) { append_role<DT>(a, bid); return; }
+      bid -= heads;
+    }
+    if (a.roles & ROLE_CORR) {
+      if (bid < heads) { corr_role<DT, G>(a, bid); return; }
+      bid -= heads;
+    }
+    head = bid / a.blocks_per_head;
+    const int chunk = bid % a.blocks_per_head;
+    if (chunk == 0) FKV_STAMP(a, head, 0);
+    score_role<DT, G>(a, head, chunk);
+    if (chunk == 0) FKV_STAMP(a, head, 1);
+    if (!a.fuse_select) return;
+    if (!last_block_done(a.counters + head, a.blocks_per_head)) return;
+  }
+  FKV_STAMP(a, head, 2);
+  if (a.staged) select_block<G, true>(a, head, dyn_lds);
+  else          select_block<G, false>(a, head, dyn_lds);
+  FKV_STAMP(a, head, 8);
+  if (a.sel_done) {
+    // the ids went out with device-scope stores; once they are acknowledged, announce them
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(a.sel_done + head, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+}  // namespace fkv
