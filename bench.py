@@ -101,6 +101,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (stated in config.workload)")
     ap.add_argument("--placement", type=int, default=-1, help="override KV placement: 0 HBM, 1 pinned host pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--standin-mb", type=int, default=0,
+                    help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
+                         "a labelled stand-in for the layer's QKV/FFN weight reads that recall overlaps with in a "
+                         "real model (never part of the default run)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run a plain elementwise kernel of known size (reads and writes 256 MiB) three "
                          "times: the yardstick for HBM byte counters collected over this command")
@@ -145,11 +149,18 @@ def main():
     stream = torch.cuda.current_stream()
     copy_stream = torch.cuda.Stream()
 
+    standin = None
+    if args.standin_mb > 0:
+        standin = torch.ones(args.standin_mb * 1000 * 1000 // 2, dtype=torch.bfloat16, device=dev)
+        sink_val = torch.zeros((1,), dtype=torch.float32, device=dev)
+
     def run(t0, t1):
         for t in range(t0, t1):
             for layer in range(wl.n_layers):
                 ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer],
                                 stream=stream, copy_stream=copy_stream)
+                if standin is not None:
+                    torch.sum(standin, dim=(0,), keepdim=True, dtype=torch.float32, out=sink_val)
 
     run(0, Wm)
     torch.cuda.synchronize()
@@ -191,6 +202,18 @@ def main():
         extra = {"page_miss_rate": miss / max(picked, 1),
                  "recall_bytes_per_layer_step": miss / max(n_probe * wl.n_layers, 1) * 16384}
         extra["recall_GBps_if_exposed"] = extra["recall_bytes_per_layer_step"] / (elapsed / (K * wl.n_layers)) / 1e9
+        # the host link's own rate: a plain 1 GiB pinned -> device copy
+        src = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        dst.copy_(src, non_blocking=True)
+        c1.record()
+        torch.cuda.synchronize()
+        extra["pinned_copy_GBps"] = (1 << 30) / (c0.elapsed_time(c1) / 1e3) / 1e9
+        del src, dst
 
     layer_steps = K * wl.n_layers
     score_b, attn_b = algorithmic_bytes(wl)
@@ -227,7 +250,8 @@ def main():
                                f"KV {'in HBM' if wl.placement == 0 else 'in pinned host memory'}",
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
-                   "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9, **extra},
+                   "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9,
+                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}), **extra},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,

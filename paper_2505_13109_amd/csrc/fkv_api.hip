@@ -529,9 +529,13 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   const bool host_pool = ctx->cfg.placement == FKV_PLACE_HOST;
   bool deferred = false;
   if (host_pool) {
+    // corrected heads: recall before this step's attention (Sec. 3.3)
+    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_FLAGGED, compute_stream);
+    if (rc) return rc;
     // other heads: recall for the next step on the copy stream, off the critical path
-    // (Sec. 3.2).  It needs the plan just made and writes only slots that neither this
-    // step's attention nor the corrected heads' recall touch, so it may start right here.
+    // (Sec. 3.2).  It writes only slots that this step's attention does not read, so it may run
+    // beside it; it starts behind the corrected heads' recall so that it does not share the
+    // host link with the transfer the attention is waiting for.
     if (cs != st) {
       FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
       FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
@@ -540,9 +544,6 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
       FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
       deferred = true;     // the next step of this layer waits for it, not this step's attention
     }
-    // corrected heads: recall before this step's attention (Sec. 3.3)
-    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_FLAGGED, compute_stream);
-    if (rc) return rc;
   }
   rc = fkv_sparse_decode_attn(ctx, layer, q_dev, out_dev, FKV_USE_BY_FLAG, compute_stream);
   if (rc) return rc;

@@ -107,26 +107,39 @@ __global__ __launch_bounds__(256) void offload_kernel(PoolDesc pd, uint16_t* __r
 }
 
 // ---- recall: copy missing pages host pool -> free page-cache slots ---------------
-// miss: [batch][n_kv][1 + 2k] = count, then k page ids, then k slots.  grid (k, n_kv, batch), 256 threads.
-__global__ __launch_bounds__(256) void gather_kernel(PoolDesc pd, const uint16_t* __restrict__ host_pool,
-                                                     const int32_t* __restrict__ miss,
-                                                     const uint8_t* __restrict__ flags, int heads, int k,
-                                                     int n_kv, int max_pages) {
-  const int i = blockIdx.x, m = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
-  const int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 2 * k);
-  if (i >= mh[0]) return;
-  if (heads != 0) {
-    const bool flagged = flags[b * n_kv + m] != 0;
-    if ((heads == 1) != flagged) return;
+// miss: [heads][1 + 2k] = count, then k page ids, then k slots.
+// A few 1024-thread blocks walk the miss lists, four 16 KiB units in flight per block.  Loads
+// from host memory take microseconds to return and hold up the memory pipeline of the compute
+// unit they are issued from, so the blocks are kept few and each one claims a whole compute
+// unit's LDS: no block of a kernel that uses LDS (attention, scoring) can share that unit.
+constexpr int GATHER_THREADS = 1024;
+__global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, const uint16_t* __restrict__ host_pool,
+                                                                const int32_t* __restrict__ miss,
+                                                                const uint8_t* __restrict__ flags, int heads_mode,
+                                                                int k, int n_kv, int n_heads, int max_pages) {
+  const int tid = threadIdx.x;
+  for (int head = blockIdx.x; head < n_heads; head += gridDim.x) {
+    if (heads_mode != 0) {
+      const bool flagged = flags[head] != 0;
+      if ((heads_mode == 1) != flagged) continue;
+    }
+    const int32_t* mh = miss + (size_t)head * (1 + 2 * k);
+    const int n = mh[0];
+    const uint16_t* src_head = host_pool + (size_t)head * max_pages * UNIT_ELEMS;
+    uint16_t* dst_head = pd.pool + ((size_t)head * pd.units_per_head + pd.sel_base) * UNIT_ELEMS;
+    for (int i0 = 0; i0 < n; i0 += 4) {
+      uint4 w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = min(i0 + u, n - 1);
+        w[u] = reinterpret_cast<const uint4*>(src_head + (size_t)mh[1 + i] * UNIT_ELEMS)[tid];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i0 + u < n) reinterpret_cast<uint4*>(dst_head + (size_t)mh[1 + k + i0 + u] * UNIT_ELEMS)[tid] = w[u];
+      }
+    }
   }
-  const int page = mh[1 + i], slot = mh[1 + k + i];
-  const uint4* src = reinterpret_cast<const uint4*>(host_pool + ((size_t)(b * n_kv + m) * max_pages + page) * UNIT_ELEMS);
-  uint4* dst = reinterpret_cast<uint4*>(pd.pool + (head_base(pd, b, m, n_kv) + pd.sel_base + slot) * UNIT_ELEMS);
-  uint4 w[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) w[j] = src[tid + j * 256];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) dst[tid + j * 256] = w[j];
 }
 
 // ---- recall plan: which picked pages are already cached, where the others go ------
@@ -227,8 +240,16 @@ void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, 
 void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
                    const int32_t*, const uint8_t* flags, int heads, hipStream_t st) {
   if (d.k == 0) return;
-  dim3 grid(d.k, d.n_kv, d.batch);
-  gather_kernel<<<grid, 256, 0, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, d.max_pages);
+  static bool raised = false;
+  const int hog = d.max_lds > 64 * 1024 ? d.max_lds - 1024 : 64 * 1024 - 1024;   // (nearly) all of a unit's LDS
+  if (!raised) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, hog);
+    (void)hipGetLastError();
+    raised = true;
+  }
+  const int n_heads = d.batch * d.n_kv;
+  const int blocks = n_heads < 16 ? n_heads : 16;
+  gather_kernel<<<blocks, GATHER_THREADS, hog, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, n_heads, d.max_pages);
 }
 
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st) {
