@@ -16,9 +16,11 @@ static int g_pps_override = [] { const char* e = getenv("FKV_ATTN_PPS"); return 
 
 // pages per block of NW waves for a head with n_att attended pages
 int attn_pages_per_block(int n_att, int heads, int max_splits, int nw) {
-  // a page per wave and pass; at most 32 splits per KV head so that the merge needs one round
-  // trip, unless that leaves most of the chip without a block
+  // a page per wave and pass; more pages per block (the page loop is pipelined, the merge gets
+  // cheaper) as long as the launch keeps at least ~128 blocks, and never more than 32 splits
+  // per KV head beyond that, so that the merge needs one round trip
   int pps = nw;
+  while (pps < 16 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
   while ((n_att + pps - 1) / pps > 32 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
   while ((n_att + pps - 1) / pps > (max_splits < MAX_MERGE_SPLITS ? max_splits : MAX_MERGE_SPLITS)) pps *= 2;
   if (g_pps_override > 0) pps = g_pps_override;

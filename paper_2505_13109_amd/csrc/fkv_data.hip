@@ -145,55 +145,77 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, con
 // ---- recall plan: which picked pages are already cached, where the others go ------
 // A page hits iff it is in the ACTIVE selection (it keeps that slot).  Misses go, in
 // ascending page order, to the lowest-numbered slots the ACTIVE selection does not use.
-// grid (n_kv, batch), 64 threads; pool of 2k slots per head.
+// grid (n_kv, batch), 64 threads (one wave); pool of 2k slots per head; k <= 1024.
 __global__ __launch_bounds__(64) void plan_kernel(const int32_t* __restrict__ new_ids,
                                                   const int32_t* __restrict__ act_ids,
                                                   const int32_t* __restrict__ act_slots,
                                                   int32_t* __restrict__ new_slots,
                                                   int32_t* __restrict__ miss, int k, int n_kv) {
-  extern __shared__ int32_t sm[];          // used[2k], nslot[k]
+  extern __shared__ int32_t sm[];          // used[2k], aid[k], aslot[k], nid[k], nslot[k], freelist[2k]
   int32_t* used = sm;
-  int32_t* nslot = sm + 2 * k;
-  const int m = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  int32_t* aid = sm + 2 * k;
+  int32_t* aslot = aid + k;
+  int32_t* nid = aslot + k;
+  int32_t* nslot = nid + k;
+  int32_t* freelist = nslot + k;
+  const int m = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
   const size_t hb = (size_t)(b * n_kv + m) * k;
   int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 2 * k);
-  for (int s = tid; s < 2 * k; s += 64) used[s] = 0;
-  __syncthreads();
+  for (int s = lane; s < 2 * k; s += 64) used[s] = 0;
   int n_act = 0;
-  for (int i = tid; i < k; i += 64)
-    if (act_ids[hb + i] >= 0) used[act_slots[hb + i]] = 1;
-  for (int i = 0; i < k; ++i) n_act += (act_ids[hb + i] >= 0);   // ids are ascending, -1 padded at the end
+  for (int i = lane; i < k; i += 64) {     // all lists in one round trip
+    aid[i] = act_ids[hb + i];
+    aslot[i] = act_slots[hb + i];
+    nid[i] = new_ids[hb + i];
+  }
   __syncthreads();
-  for (int i = tid; i < k; i += 64) {
-    const int id = new_ids[hb + i];
+  for (int i = lane; i < k; i += 64) {
+    if (aid[i] >= 0) { used[aslot[i]] = 1; ++n_act; }
+  }
+  n_act = (int)wave_sum_u32((uint32_t)n_act);   // ids are ascending, -1 padded at the end
+  __syncthreads();
+  // hit or miss per picked page (binary search in the ACTIVE ids)
+  for (int i = lane; i < k; i += 64) {
+    const int id = nid[i];
     int slot = -1;
     if (id >= 0) {
       int lo = 0, hi = n_act;
       while (lo < hi) {
         const int mid = (lo + hi) >> 1;
-        if (act_ids[hb + mid] < id) lo = mid + 1; else hi = mid;
+        if (aid[mid] < id) lo = mid + 1; else hi = mid;
       }
-      slot = (lo < n_act && act_ids[hb + lo] == id) ? act_slots[hb + lo] : -2;   // -2: miss
+      slot = (lo < n_act && aid[lo] == id) ? aslot[lo] : -2;   // -2: miss
     }
     nslot[i] = slot;
   }
-  __syncthreads();
-  if (tid == 0) {
-    int n_miss = 0, s = 0;
-    for (int i = 0; i < k; ++i) {
-      if (nslot[i] == -2) {
-        while (used[s]) ++s;           // at most k slots are in use, 2k exist
-        nslot[i] = s;
-        mh[1 + n_miss] = new_ids[hb + i];
-        mh[1 + k + n_miss] = s;
-        ++n_miss;
-        ++s;
-      }
-    }
-    mh[0] = n_miss;
+  // ordered list of free slots
+  int base = 0;
+  for (int s0 = 0; s0 < 2 * k; s0 += 64) {
+    const int s = s0 + lane;
+    const uint32_t f = (s < 2 * k && !used[s]) ? 1u : 0u;
+    const uint32_t incl = wave_scan_u32(f);
+    if (f) freelist[base + (int)incl - 1] = s;
+    base += (int)__builtin_amdgcn_readlane((int)incl, 63);
   }
   __syncthreads();
-  for (int i = tid; i < k; i += 64) new_slots[hb + i] = nslot[i];
+  // the r-th miss (ascending page id) takes the r-th free slot
+  int n_miss = 0;
+  for (int i0 = 0; i0 < k; i0 += 64) {
+    const int i = i0 + lane;
+    const uint32_t f = (i < k && nslot[i] == -2) ? 1u : 0u;
+    const uint32_t incl = wave_scan_u32(f);
+    if (f) {
+      const int r = n_miss + (int)incl - 1;
+      const int s = freelist[r];
+      nslot[i] = s;
+      mh[1 + r] = nid[i];
+      mh[1 + k + r] = s;
+    }
+    n_miss += (int)__builtin_amdgcn_readlane((int)incl, 63);
+  }
+  if (lane == 0) mh[0] = n_miss;
+  __syncthreads();
+  for (int i = lane; i < k; i += 64) new_slots[hb + i] = nslot[i];
 }
 
 // ---- debug: one unit -> token-major K [p, d], V [p, d] ---------------------------
@@ -234,7 +256,7 @@ void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, 
                  int32_t* new_slots, int32_t* miss, hipStream_t st) {
   if (d.k == 0) return;
   dim3 grid(d.n_kv, d.batch);
-  plan_kernel<<<grid, 64, 3 * d.k * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv);
+  plan_kernel<<<grid, 64, 8 * d.k * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv);
 }
 
 void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
