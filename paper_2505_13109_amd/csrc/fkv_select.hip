@@ -38,7 +38,15 @@ static bool raise_lds(size_t lds) {
 // it is small the selection rides in the scoring launch (its last block per head runs it);
 // when it would limit how many scoring blocks fit a compute unit, scoring runs without it and
 // a second launch of one block per head selects.
-constexpr size_t kFuseLdsLimit = 40 * 1024;
+constexpr size_t kLdsPerUnit = 150 * 1024;   // of the 160 KiB of a compute unit
+constexpr int kComputeUnits = 256;
+// may every block of a `grid`-block launch carry `lds` bytes without starving the scoring blocks?
+static bool lds_fits_launch(size_t lds, int grid) {
+  int per_unit = (grid + kComputeUnits - 1) / kComputeUnits;   // blocks a unit should hold at once
+  if (per_unit < 1) per_unit = 1;
+  if (per_unit > 4) per_unit = 4;
+  return lds * per_unit <= kLdsPerUnit;
+}
 
 template <int DT, int G>
 static void launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
@@ -51,7 +59,7 @@ static void launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, s
     a.staged = 0;
   }
   if (select && !a.staged && lds > kDefaultLimit) (void)raise_lds<DT, G>(lds);
-  a.fuse_select = (select && lds <= kFuseLdsLimit) ? 1 : 0;
+  a.fuse_select = (select && lds_fits_launch(lds, grid)) ? 1 : 0;
   a.select_only = 0;
   step_kernel<DT, G><<<grid, STEP_THREADS, a.fuse_select ? lds : 0, st>>>(a);
   if (select && !a.fuse_select) {
@@ -70,7 +78,7 @@ static void launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_s
   }
 }
 
-static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, StepArgs& a, int& grid,
+static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, int passes, StepArgs& a, int& grid,
                            size_t& lds_staged, size_t& lds_keys) {
   a = StepArgs{};
   a.roles = roles;
@@ -81,7 +89,8 @@ static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, S
   a.flags = io.flags; a.flags_user = io.flags_user; a.cosine = io.cosine;
   a.P = io.P; a.score = io.score; a.ids = io.ids; a.ids_user = io.ids_user; a.counters = io.counters; a.tstamp = io.tstamp;
   const int heads = d.batch * d.n_kv;
-  a.blocks_per_head = g.n_cand > 0 ? (g.n_cand + PAGES_PER_BLOCK - 1) / PAGES_PER_BLOCK : 1;
+  a.passes = passes;
+  a.blocks_per_head = g.n_cand > 0 ? (g.n_cand + PAGES_PER_PASS * passes - 1) / (PAGES_PER_PASS * passes) : 1;
   grid = 0;
   lds_staged = lds_keys = 0;
   if (roles & ROLE_APPEND) grid += heads;
@@ -112,7 +121,7 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
   StepArgs a;
   int grid;
   size_t lds_staged, lds_keys;
-  fill_step_args(d, roles, io, g, a, grid, lds_staged, lds_keys);
+  fill_step_args(d, roles, io, g, 1, a, grid, lds_staged, lds_keys);
   if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
   else              launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
 }
@@ -145,40 +154,57 @@ __global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
 static bool g_no_layer_kernel = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '1'; }();
 
 template <int DT, int G>
-static void launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
+static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
+  static size_t granted = 48 * 1024;      // dynamic LDS beyond the default has to be granted per function
+  if (lds > granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<DT, G>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    granted = lds;
+  }
   layer_kernel<DT, G><<<grid, STEP_THREADS, lds, st>>>(a);
+  return true;
 }
 
 bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, hipStream_t st) {
   const int roles = ROLE_APPEND | ROLE_CORR | ROLE_SELECT;
   if (g_no_layer_kernel || io.pd.placement != 0 || d.k == 0 || append_races_selection(roles, g)) return false;
   LayerArgs a{};
-  int grid;
-  size_t lds_staged, lds_keys;
-  fill_step_args(d, roles, io, g, a.s, grid, lds_staged, lds_keys);
-  if (lds_staged > kFuseLdsLimit) return false;           // big selections keep their own launches
-  a.s.staged = lds_staged > lds_keys ? 1 : 0;
-  a.s.fuse_select = 1;
-  a.s.select_only = 0;
-  a.s.sel_done = lio.sel_done;
-  a.s.epoch = lio.epoch;
-  const int heads = d.batch * d.n_kv;
-  const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
-  AttnArgs& at = a.at;
-  at.pd = io.pd; at.q = io.q; at.act_ids = lio.act_ids; at.new_ids = io.ids; at.act_slots = nullptr; at.new_slots = nullptr;
-  at.flags = io.flags; at.use = 2; at.part_o = lio.part_o; at.part_ml = lio.part_ml; at.max_splits = lio.max_splits;
-  at.pps = attn_pages_per_block(n_att, heads, lio.max_splits, STEP_WAVES);
-  at.n_splits = (n_att + at.pps - 1) / at.pps;
-  at.counters = lio.attn_counters; at.out = lio.out; at.g = g;
-  at.n_q = d.n_q; at.n_kv = d.n_kv; at.G = d.G; at.k = d.k; at.tstamp = io.tstamp;
-  at.fused = 1; at.q_prev = io.q_prev; at.have_prev = io.have_prev; at.tau = io.tau;
-  at.k_new = io.k_new; at.v_new = io.v_new; at.sel_done = lio.sel_done; at.epoch = lio.epoch; at.status = lio.status;
-  a.attn_block0 = grid;
-  grid += heads * at.n_splits;
-  const size_t lds_attn = (size_t)STEP_WAVES * (32 + d.G * D) * sizeof(float);
-  const size_t lds = lds_staged > lds_attn ? lds_staged : lds_attn;
+  int grid = 0;
+  size_t lds = 0;
+  bool fits = false;
+  // fewer, fatter scoring blocks if that is what lets every block of the launch carry the
+  // selection's LDS
+  for (int passes = 1; passes <= SCORE_PASSES && !fits; passes *= 2) {
+    size_t lds_staged, lds_keys;
+    fill_step_args(d, roles, io, g, passes, a.s, grid, lds_staged, lds_keys);
+    a.s.staged = lds_staged > lds_keys ? 1 : 0;
+    a.s.fuse_select = 1;
+    a.s.select_only = 0;
+    a.s.sel_done = lio.sel_done;
+    a.s.epoch = lio.epoch;
+    const int heads = d.batch * d.n_kv;
+    const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
+    AttnArgs& at = a.at;
+    at.pd = io.pd; at.q = io.q; at.act_ids = lio.act_ids; at.new_ids = io.ids; at.act_slots = nullptr; at.new_slots = nullptr;
+    at.flags = io.flags; at.use = 2; at.part_o = lio.part_o; at.part_ml = lio.part_ml; at.max_splits = lio.max_splits;
+    at.pps = attn_pages_per_block(n_att, heads, lio.max_splits, STEP_WAVES);
+    at.n_splits = (n_att + at.pps - 1) / at.pps;
+    at.counters = lio.attn_counters; at.out = lio.out; at.g = g;
+    at.n_q = d.n_q; at.n_kv = d.n_kv; at.G = d.G; at.k = d.k; at.tstamp = io.tstamp;
+    at.fused = 1; at.q_prev = io.q_prev; at.have_prev = io.have_prev; at.tau = io.tau;
+    at.k_new = io.k_new; at.v_new = io.v_new; at.sel_done = lio.sel_done; at.epoch = lio.epoch; at.status = lio.status;
+    a.attn_block0 = grid;
+    grid += heads * at.n_splits;
+    const size_t lds_attn = (size_t)STEP_WAVES * (32 + d.G * D) * sizeof(float);
+    lds = lds_staged > lds_attn ? lds_staged : lds_attn;
+    fits = lds_fits_launch(lds, grid);
+  }
+  if (!fits) return false;                                 // big selections keep their own launches
   switch (d.G) {
-#define FKV_CASE(GG) case GG: if (d.dtype == 0) launch_layer_g<0, GG>(a, grid, lds, st); else launch_layer_g<1, GG>(a, grid, lds, st); break;
+#define FKV_CASE(GG) case GG: return d.dtype == 0 ? launch_layer_g<0, GG>(a, grid, lds, st) : launch_layer_g<1, GG>(a, grid, lds, st);
     FKV_CASE(1) FKV_CASE(2) FKV_CASE(3) FKV_CASE(4) FKV_CASE(5) FKV_CASE(6) FKV_CASE(7) FKV_CASE(8)
 #undef FKV_CASE
     default: return false;

@@ -29,13 +29,12 @@ namespace fkv {
 #define FKV_STEP_THREADS 512
 #endif
 #ifndef FKV_SCORE_PASSES
-#define FKV_SCORE_PASSES 1
+#define FKV_SCORE_PASSES 4
 #endif
 constexpr int STEP_THREADS = FKV_STEP_THREADS;         // >= 256 (the radix histograms have 256 bins)
 constexpr int STEP_WAVES = STEP_THREADS / 64;
-constexpr int SCORE_PASSES = FKV_SCORE_PASSES;
+constexpr int SCORE_PASSES = FKV_SCORE_PASSES;         // most passes a scoring block can make (StepArgs::passes <= this)
 constexpr int PAGES_PER_PASS = STEP_WAVES * 4;         // a wave scores 4 pages per pass
-constexpr int PAGES_PER_BLOCK = PAGES_PER_PASS * SCORE_PASSES;
 
 struct StepArgs {
   int roles;                 // ROLE_* bits
@@ -62,6 +61,7 @@ struct StepArgs {
   int32_t* ids_user;
   int* counters;
   int blocks_per_head;
+  int passes;                // passes of PAGES_PER_PASS pages a scoring block makes (1 .. SCORE_PASSES)
   int staged;                // the G x n_cand weights fit in LDS next to the keys
   int fuse_select;           // the last scoring block of a head runs its selection (else: a second launch does)
   int select_only;           // this launch: one block per head, selection only
@@ -137,14 +137,15 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
   const int b = head / a.n_kv, m = head % a.n_kv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane >> 4, c8 = lane & 15;
-  if (chunk * PAGES_PER_BLOCK >= a.g.n_cand) return;      // a block that only exists to run the selection
+  const int pages_per_block = PAGES_PER_PASS * a.passes;
+  if (chunk * pages_per_block >= a.g.n_cand) return;      // a block that only exists to run the selection
   // all summary loads of the block's passes first, then q: everything is in flight at once
   uint4 wmax[SCORE_PASSES], wmin[SCORE_PASSES];
   int page[SCORE_PASSES];
 #pragma unroll
   for (int ps = 0; ps < SCORE_PASSES; ++ps) {
-    const int j = chunk * PAGES_PER_BLOCK + ps * PAGES_PER_PASS + wave * 4 + grp;
-    page[ps] = j < a.g.n_cand ? a.g.cand_lo + j : -1;
+    const int j = chunk * pages_per_block + ps * PAGES_PER_PASS + wave * 4 + grp;
+    page[ps] = (ps < a.passes && j < a.g.n_cand) ? a.g.cand_lo + j : -1;
     const int pg = a.g.cand_lo + (j < a.g.n_cand ? j : 0);
     wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
     wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
@@ -158,6 +159,7 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
   const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
 #pragma unroll
   for (int ps = 0; ps < SCORE_PASSES; ++ps) {
+    if (ps >= a.passes) break;
     float kx[8], kn[8];
     unpack8<DT>(wmax[ps], kx);
     unpack8<DT>(wmin[ps], kn);
