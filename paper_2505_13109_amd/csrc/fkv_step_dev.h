@@ -147,8 +147,10 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
     const int j = chunk * pages_per_block + ps * PAGES_PER_PASS + wave * 4 + grp;
     page[ps] = (ps < a.passes && j < a.g.n_cand) ? a.g.cand_lo + j : -1;
     const int pg = a.g.cand_lo + (j < a.g.n_cand ? j : 0);
-    wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
-    wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
+    if (ps < a.passes) {
+      wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
+      wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
+    }
   }
   float f[G][8];
 #pragma unroll
