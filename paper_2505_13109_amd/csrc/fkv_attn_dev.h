@@ -96,12 +96,15 @@ struct AttendList {
   int n_sink, k, n_win, n_full, r;
   bool coherent_ids;         // ids written earlier in this very launch: read them at device scope
 };
-__device__ __forceinline__ int attend_unit(const AttendList& al, const PoolDesc& pd, int i, int& n_valid, int& page) {
+// have_id: the page id of position i was fetched earlier (`id`), do not load it again
+__device__ __forceinline__ int attend_unit(const AttendList& al, const PoolDesc& pd, int i, int& n_valid, int& page,
+                                           bool have_id = false, int id_in = -1) {
   n_valid = PG;
   if (i < al.n_sink) { page = i; return i; }
   i -= al.n_sink;
   if (i < al.k) {
-    const int id = al.coherent_ids ? __hip_atomic_load(al.ids + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : al.ids[i];
+    const int id = have_id ? id_in
+                 : al.coherent_ids ? __hip_atomic_load(al.ids + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : al.ids[i];
     page = id;
     if (id < 0) return -1;
     return pd.placement == 0 ? id : pd.sel_base + al.slots[i];
@@ -140,6 +143,13 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
       qv[s] = __builtin_bit_cast(vec, w);
     }
   }
+
+  // In a fused launch the common case is "no correction": fetch the first page id of this wave
+  // from the ACTIVE list now, together with the loads of the correction test, instead of after it.
+  const int pos0 = split * a.pps + wave;
+  const bool spec = a.fused && pos0 >= g.n_sink && pos0 < g.n_sink + k;
+  int spec_id = -1;
+  if (spec) spec_id = a.act_ids[(size_t)head * k + pos0 - g.n_sink];
 
   bool pending;
   if (a.fused) {
@@ -199,8 +209,12 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
   // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
   const int p_end = min(n_att, (split + 1) * a.pps);
-  int pos = split * a.pps + wave, unit = -1, n_valid = PG, page = -1;
-  while (pos < p_end && (unit = attend_unit(al, pd, pos, n_valid, page)) < 0) pos += NW;
+  int pos = pos0, unit = -1, n_valid = PG, page = -1;
+  if (pos < p_end) unit = attend_unit(al, pd, pos, n_valid, page, spec && !pending, spec_id);
+  if (unit < 0) {
+    pos += NW;
+    while (pos < p_end && (unit = attend_unit(al, pd, pos, n_valid, page)) < 0) pos += NW;
+  }
   uint4 kw[8], vw[8];
   if (unit >= 0) {
     const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)unit * UNIT_ELEMS) + lane;

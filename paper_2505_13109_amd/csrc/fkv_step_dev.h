@@ -228,9 +228,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
   uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
   constexpr bool staged = STAGED;                      // else: re-read the weights from memory in each pass
-  long long tk[8];
-#define FKV_TK(i) do { if (a.tstamp) tk[i] = clock64(); } while (0)
-  FKV_TK(0);
 #pragma unroll
   for (int p = 0; p < 4; ++p)
     if (tid < 256) hist[p][tid] = 0;
@@ -273,7 +270,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_redf[w][gg]);
     mx[gg] = v;
   }
-  FKV_TK(1);
   // fixed-point softmax numerators in place, integer denominators (a sum of integers: no order to fix)
   unsigned long long z[G];
 #pragma unroll
@@ -314,7 +310,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     for (int w = 0; w < STEP_WAVES; ++w) v += s_redz[w][gg];
     zd[gg] = (double)v;
   }
-  FKV_TK(2);
   // pooled score of each candidate (each thread reads back only what it wrote); the top
   // byte of its key goes straight into the first histogram
   for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {
@@ -342,7 +337,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   }
   __syncthreads();
 
-  FKV_TK(3);
   // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
   // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
   uint32_t prefix = 0, remaining = (uint32_t)kk;
@@ -374,7 +368,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
     prefix = (prefix << 8) | bin;
   }
-  FKV_TK(4);
   const uint32_t T = prefix;                         // the kk-th largest key
   const uint32_t take_eq = remaining;                // keys equal to T to take, lowest ids first
 
@@ -403,8 +396,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     gt_before += (kj > T);
     eq_before += (kj == T);
   }
-  FKV_TK(5);
-  if (a.tstamp && head == 0 && tid == 0) for (int i = 0; i < 6; ++i) a.tstamp[40 + i] = tk[i];
   for (int i = kk + tid; i < k; i += STEP_THREADS) {   // padding
     __hip_atomic_store(out + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (outu) outu[i] = -1;
