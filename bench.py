@@ -99,6 +99,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="c2", help="c2 is the benchmark workload; the others are for the design notes")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (stated in config.workload)")
+    ap.add_argument("--recall-mode", type=int, default=0, help="placement 1: 0 gather kernel, 1 hipMemcpyAsync per unit")
     ap.add_argument("--placement", type=int, default=-1, help="override KV placement: 0 HBM, 1 pinned host pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--standin-mb", type=int, default=0,
@@ -137,7 +138,7 @@ def main():
     max_ctx = ((wl.ctx + 2 * n_steps + 16 + p - 1) // p) * p   # the steps are run twice (timed, then with kernel timers)
     ctx = fkv.FreeKV(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                      max_ctx=max_ctx, budget=wl.budget, sink=wl.sink, window=wl.window, tau=wl.tau,
-                     dtype=wl.dtype, placement=wl.placement)
+                     dtype=wl.dtype, placement=wl.placement, recall_mode=args.recall_mode)
     kv, q, k_new, v_new = gen_inputs(torch, wl, n_steps, dev)
     for layer in range(wl.n_layers):
         Kp = kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim))
@@ -199,7 +200,8 @@ def main():
                 m = ctx.debug_read(layer, B.DBG_MISS)
                 miss += int(m[..., 0].sum())
                 picked += wl.batch * wl.n_kv_heads * wl.k_pages
-        extra = {"page_miss_rate": miss / max(picked, 1),
+        extra = {"recall_mode": "hipMemcpyAsync per unit" if args.recall_mode else "gather kernel",
+                 "page_miss_rate": miss / max(picked, 1),
                  "recall_bytes_per_layer_step": miss / max(n_probe * wl.n_layers, 1) * 16384}
         extra["recall_GBps_if_exposed"] = extra["recall_bytes_per_layer_step"] / (elapsed / (K * wl.n_layers)) / 1e9
         # the host link's own rate: a plain 1 GiB pinned -> device copy

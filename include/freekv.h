@@ -52,6 +52,12 @@ extern "C" {
 #define FKV_PLACE_HOST 1  /* whole KV cache in a pinned host pool; HBM holds sink,
                              window and a double-buffered cache of picked pages    */
 
+/* how fkv_recall_pages moves a missing page (placement HOST) */
+#define FKV_RECALL_GATHER  0  /* a kernel reads the pinned pool through its device address;
+                                 page ids never leave the device, no host synchronisation       */
+#define FKV_RECALL_MEMCPY  1  /* one hipMemcpyAsync per 16 KiB unit on the copy stream; the miss
+                                 list is first copied to the host and the call BLOCKS on it      */
+
 /* which page list sparse attention reads */
 #define FKV_USE_ACTIVE   0  /* pages committed at the previous step (reuse)        */
 #define FKV_USE_PENDING  1  /* pages picked at this step                           */
@@ -78,7 +84,7 @@ typedef struct {
   int32_t dtype;           /* FKV_DTYPE_*                                           */
   int32_t placement;       /* FKV_PLACE_*                                           */
   float   tau;             /* correction threshold; <= -1 never corrects, > 1 always */
-  int32_t reserved;        /* 0                                                     */
+  int32_t recall_mode;     /* FKV_RECALL_* (placement HOST)                         */
 } fkv_config;
 
 /* Bytes the library needs: a device arena, and (placement HOST) a pinned,

@@ -8,6 +8,6 @@ context does not.
 from .binding import (  # noqa: F401
     FKV_DTYPE_FP16, FKV_DTYPE_BF16, FKV_PLACE_HBM, FKV_PLACE_HOST,
     FKV_USE_ACTIVE, FKV_USE_PENDING, FKV_USE_BY_FLAG,
-    FKV_HEADS_ALL, FKV_HEADS_FLAGGED, FKV_HEADS_UNFLAGGED,
+    FKV_HEADS_ALL, FKV_HEADS_FLAGGED, FKV_HEADS_UNFLAGGED, FKV_RECALL_GATHER, FKV_RECALL_MEMCPY,
     FkvConfig, FreeKV, FreeKVError, lib, lib_path, EXPORTED_SYMBOLS,
 )

@@ -15,6 +15,7 @@ FKV_DTYPE_FP16, FKV_DTYPE_BF16 = 0, 1
 FKV_PLACE_HBM, FKV_PLACE_HOST = 0, 1
 FKV_USE_ACTIVE, FKV_USE_PENDING, FKV_USE_BY_FLAG = 0, 1, 2
 FKV_HEADS_ALL, FKV_HEADS_FLAGGED, FKV_HEADS_UNFLAGGED = 0, 1, 2
+FKV_RECALL_GATHER, FKV_RECALL_MEMCPY = 0, 1
 DBG_SUMMARIES, DBG_WEIGHTS, DBG_SCORES, DBG_ACTIVE_IDS, DBG_PENDING_IDS, DBG_FLAGS, DBG_MISS, DBG_COSINE, DBG_TSTAMP = range(9)
 
 EXPORTED_SYMBOLS = (
@@ -35,7 +36,7 @@ class FkvConfig(C.Structure):
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
         ("max_ctx", C.c_int32), ("budget_tokens", C.c_int32), ("sink_tokens", C.c_int32),
         ("window_tokens", C.c_int32), ("dtype", C.c_int32), ("placement", C.c_int32),
-        ("tau", C.c_float), ("reserved", C.c_int32),
+        ("tau", C.c_float), ("recall_mode", C.c_int32),
     ]
 
 
@@ -102,12 +103,13 @@ class FreeKV:
     """One context.  Methods carry the names of the C entry points they call."""
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, max_ctx, budget, sink, window,
-                 tau, dtype="bf16", placement=FKV_PLACE_HBM, head_dim=128, page_size=32, device="cuda:0"):
+                 tau, dtype="bf16", placement=FKV_PLACE_HBM, head_dim=128, page_size=32, device="cuda:0",
+                 recall_mode=0):
         import torch
         self._torch = torch
         self.L = lib()
         self.cfg = FkvConfig(n_layers, batch, n_q_heads, n_kv_heads, head_dim, page_size, max_ctx,
-                             budget, sink, window, {"fp16": 0, "bf16": 1}[dtype], placement, tau, 0)
+                             budget, sink, window, {"fp16": 0, "bf16": 1}[dtype], placement, tau, recall_mode)
         self.dtype = dtype
         self.torch_dtype = torch.float16 if dtype == "fp16" else torch.bfloat16
         self.k = (budget - sink - window) // page_size

@@ -93,6 +93,7 @@ const char* check_config(const fkv_config* c) {
   if ((size_t)(c->max_ctx / PG) * 4 + 4096 > 65536) return "max_ctx above 503808 tokens is not supported (top-k keys live in LDS)";
   if ((c->budget_tokens - c->sink_tokens - c->window_tokens) / PG > 1024) return "more than 1024 selectable pages are not supported";
   if (c->tau != c->tau) return "tau is NaN";
+  if (c->recall_mode != FKV_RECALL_GATHER && c->recall_mode != FKV_RECALL_MEMCPY) return "bad recall_mode";
   return nullptr;
 }
 
@@ -122,6 +123,8 @@ struct fkv_ctx {
   std::vector<LayerState> layers;
   std::string err;
   hipEvent_t ev_fork = nullptr;
+  std::vector<int32_t> host_miss;     // FKV_RECALL_MEMCPY: host copies of the miss lists and flags
+  std::vector<uint8_t> host_flags;
   // optional timers around the split attention kernel (fkv_profile_*)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // begin/end pairs
@@ -434,6 +437,28 @@ int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stre
   hipStream_t cs = static_cast<hipStream_t>(copy_stream);
   if (ls.offload_outstanding) {   // a page offloaded moments ago may be picked already
     FKV_HIP(ctx, hipStreamWaitEvent(cs, ls.ev_offload, 0));
+  }
+  if (ctx->cfg.recall_mode == FKV_RECALL_MEMCPY) {
+    // the miss lists and flags come to the host (blocking), then one copy per 16 KiB unit
+    const fkv_config& c = ctx->cfg;
+    const int n_heads = c.batch * c.n_kv_heads, kk = ctx->lay.k;
+    const size_t n_int = (size_t)n_heads * (1 + 2 * kk);
+    if (ctx->host_miss.size() < n_int) ctx->host_miss.resize(n_int);
+    if (ctx->host_flags.size() < (size_t)n_heads) ctx->host_flags.resize(n_heads);
+    FKV_HIP(ctx, hipMemcpyAsync(ctx->host_miss.data(), ctx->miss(layer), n_int * 4, hipMemcpyDeviceToHost, cs));
+    FKV_HIP(ctx, hipMemcpyAsync(ctx->host_flags.data(), ctx->flags(layer), n_heads, hipMemcpyDeviceToHost, cs));
+    FKV_HIP(ctx, hipStreamSynchronize(cs));
+    const PoolDesc pd = ctx->pool_desc(layer);
+    for (int h = 0; h < n_heads; ++h) {
+      if (heads != FKV_HEADS_ALL && ((heads == FKV_HEADS_FLAGGED) != (ctx->host_flags[h] != 0))) continue;
+      const int32_t* mh = ctx->host_miss.data() + (size_t)h * (1 + 2 * kk);
+      for (int i = 0; i < mh[0]; ++i) {
+        const uint16_t* src = ctx->host_pool(layer) + ((size_t)h * ctx->lay.max_pages + mh[1 + i]) * UNIT_ELEMS;
+        uint16_t* dst = pd.pool + ((size_t)h * pd.units_per_head + pd.sel_base + mh[1 + kk + i]) * UNIT_ELEMS;
+        FKV_HIP(ctx, hipMemcpyAsync(dst, src, UNIT_BYTES, hipMemcpyHostToDevice, cs));
+      }
+    }
+    return FKV_OK;
   }
   launch_gather(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ctx->miss(layer), nullptr,
                 ctx->flags(layer), heads, cs);

@@ -33,7 +33,7 @@ def _diff(got, ref):
 class Pair:
     """One HIP context and the matching oracles for `layers` x `batch` of a workload."""
 
-    def __init__(self, wl, layers, ctx=None, placement=None, tau=None, max_ctx=None, steps=None):
+    def __init__(self, wl, layers, ctx=None, placement=None, tau=None, max_ctx=None, steps=None, recall_mode=0):
         self.wl = wl
         self.layers = list(layers)
         self.n_ctx = wl.ctx if ctx is None else ctx
@@ -45,7 +45,7 @@ class Pair:
         self.g = fkv.FreeKV(n_layers=len(self.layers), batch=wl.batch, n_q_heads=wl.n_q_heads,
                             n_kv_heads=wl.n_kv_heads, max_ctx=self.max_ctx, budget=wl.budget,
                             sink=wl.sink, window=wl.window, tau=self.tau, dtype=wl.dtype,
-                            placement=self.placement)
+                            placement=self.placement, recall_mode=recall_mode)
         self.oracles = {}
         self.q, self.kd, self.vd = {}, {}, {}
         self.copy_stream = torch.cuda.Stream()

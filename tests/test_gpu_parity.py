@@ -190,3 +190,15 @@ def test_c3_shape_host_pool_recall():
     print("c3", pr.stats)
     assert pr.stats["misses"] > 0 and pr.stats["misses"] < pr.stats["picked"]
     pr.close()
+
+
+def test_host_pool_recall_with_memcpy_per_unit():
+    """The alternative recall engine (one hipMemcpyAsync per 16 KiB unit) gives the same results."""
+    wl = W.get_workload("c3").scaled(batch=2, ctx=8192 - 11, steps=40)
+    pr = _pair(wl, [5], steps=40, recall_mode=1)
+    for t in range(40):
+        pr.step(0, t)
+    torch.cuda.synchronize()
+    pr.check_cached_pages(0, 1, 2, where=2)
+    assert pr.stats["misses"] > 0
+    pr.close()
