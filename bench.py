@@ -140,12 +140,23 @@ def main():
                      max_ctx=max_ctx, budget=wl.budget, sink=wl.sink, window=wl.window, tau=wl.tau,
                      dtype=wl.dtype, placement=wl.placement, recall_mode=args.recall_mode)
     kv, q, k_new, v_new = gen_inputs(torch, wl, n_steps, dev)
+    prefill_ms = 0.0
     for layer in range(wl.n_layers):
         Kp = kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim))
         Vp = kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim))
-        ctx.load_prefix(layer, Kp, Vp)
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        ctx.load_prefix(layer, Kp, Vp)          # bulk paging + min-max summaries (+ offload to the host pool)
+        p1.record()
         torch.cuda.synchronize()
+        if layer > 0 or wl.n_layers == 1:
+            prefill_ms += p0.elapsed_time(p1)
         del Kp, Vp
+    kv_bytes = 2 * wl.batch * wl.ctx * wl.n_kv_heads * wl.head_dim * 2
+    prefill_layers = max(wl.n_layers - 1, 1)
+    prefill = {"prefill_us_per_layer": prefill_ms / prefill_layers * 1e3,
+               # K and V read once, written once as pages, plus the summaries (2 of 32 rows of K per page)
+               "prefill_GBps_read_plus_written": (2 * kv_bytes + kv_bytes // 32) / (prefill_ms / prefill_layers / 1e3) / 1e9}
     out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
     copy_stream = torch.cuda.Stream()
@@ -253,7 +264,7 @@ def main():
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
                    "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9,
-                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}), **extra},
+                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}), **extra, **prefill},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,

@@ -10,6 +10,8 @@ A plain, slow, obviously-correct NumPy statement of what one decode step of one
   * reuse of the previous step's selection           -- Sec. 3.2 "Speculative retrieval"
   * cosine test, group mean, head-wise correction    -- Sec. 3.1 (definition of C_i), Sec. 3.3
   * which selected pages must be recalled            -- Sec. 4.1 (GPU cache of selected pages)
+  * the alternative group poolings of the selection
+    (Max/Mean over Q, QK, S) and of the correction    -- App. B.2, App. B.3
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
 module.  It shares no code with the HIP path and never calls it.
@@ -142,23 +144,66 @@ def exp_spec(x: np.ndarray) -> np.ndarray:
     return np.where(t < F32(-64.0), F32(0.0), e)
 
 
-def pooled_scores(P: np.ndarray, G: int) -> np.ndarray:
-    """score_{m,j} = (1/G) sum_g softmax_j(P^{mG+g})  (Sec. 3.2), steps d-g.  P [n_q, n_cand] -> [n_kv, n_cand] fp32."""
+SELECT_POOLINGS = ("MeanS", "MaxS", "MeanQK", "MaxQK", "MeanQ", "MaxQ")
+CORR_POOLINGS = ("mean", "max", "min")
+
+
+def pool_queries(q: np.ndarray, G: int, pooling: str) -> np.ndarray:
+    """Group-pooled query vectors (App. B.2, variants "Q"): [n_q, d] -> [n_kv, d] fp32.
+
+    MeanQ: channel-wise fp32 sum over the group in head order, divided by fl32(G);
+    MaxQ: channel-wise maximum.
+    """
+    n_q, d = q.shape
+    n_kv = n_q // G
+    q = q.astype(F32)
+    out = np.empty((n_kv, d), dtype=F32)
+    for m in range(n_kv):
+        acc = q[m * G].copy()
+        for g in range(1, G):
+            acc = (acc + q[m * G + g]) if pooling == "MeanQ" else np.maximum(acc, q[m * G + g])
+        out[m] = acc / F32(G) if pooling == "MeanQ" else acc
+    return out
+
+
+def pooled_scores(P: np.ndarray, G: int, pooling: str = "MeanS") -> np.ndarray:
+    """Group-consistent page scores: P [n_q, n_cand] -> [n_kv, n_cand] fp32.
+
+    MeanS (the method, Sec. 3.2): score_{m,j} = (1/G) sum_g softmax_j(P^{mG+g}), steps d-g.
+    Alternatives of App. B.2: MaxS (maximum over the group of the softmax values), MeanQK / MaxQK
+    (mean / maximum over the group of the weights themselves: fp32 sum in head order divided by
+    fl32(G), or the maximum), and MeanQ / MaxQ, where P already holds one row per KV head
+    (weights of the pooled query) and is the score.
+    """
+    assert pooling in SELECT_POOLINGS
+    if pooling in ("MeanQ", "MaxQ"):
+        return P.astype(F32)
     n_q, n_cand = P.shape
     n_kv = n_q // G
     if n_cand == 0:
         return np.zeros((n_kv, 0), dtype=F32)
+    score = np.empty((n_kv, n_cand), dtype=F32)
+    if pooling in ("MeanQK", "MaxQK"):
+        for m in range(n_kv):
+            acc = P[m * G].astype(F32)
+            for g in range(1, G):
+                acc = (acc + P[m * G + g]) if pooling == "MeanQK" else np.maximum(acc, P[m * G + g])
+            score[m] = acc / F32(G) if pooling == "MeanQK" else acc
+        return score
     M = P.max(axis=1, keepdims=True)
     e = exp_spec(P - M)
     E = np.rint(e * TWO31_F32).astype(np.uint64)
     Z = E.sum(axis=1)
-    score = np.empty((n_kv, n_cand), dtype=F32)
     for m in range(n_kv):
-        acc = np.zeros(n_cand, dtype=F64)
+        acc = None
         for g in range(G):
             h = m * G + g
-            acc = acc + E[h].astype(F64) / F64(Z[h])
-        score[m] = (acc / F64(G)).astype(F32)
+            s_g = E[h].astype(F64) / F64(Z[h])
+            if acc is None:
+                acc = s_g if pooling == "MaxS" else np.zeros(n_cand, dtype=F64) + s_g
+            else:
+                acc = np.maximum(acc, s_g) if pooling == "MaxS" else acc + s_g
+        score[m] = acc.astype(F32) if pooling == "MaxS" else (acc / F64(G)).astype(F32)
     return score
 
 
@@ -189,15 +234,22 @@ def query_cosine(q: np.ndarray, q_prev: np.ndarray) -> np.ndarray:
     return C
 
 
-def correction_flags(C: np.ndarray, G: int, tau: float) -> np.ndarray:
-    """A KV head is corrected iff the group mean of C is strictly below tau (Sec. 3.3)."""
+def correction_flags(C: np.ndarray, G: int, tau: float, pooling: str = "mean") -> np.ndarray:
+    """A KV head is corrected iff the group-pooled C is strictly below tau (Sec. 3.3).
+
+    pooling "mean" is the method; "max" is the alternative of App. B.3 taken literally (the largest
+    similarity of the group); "min" corrects as soon as any head of the group is below tau.
+    """
+    assert pooling in CORR_POOLINGS
     n_kv = C.shape[0] // G
     flags = np.zeros(n_kv, dtype=np.uint8)
     for m in range(n_kv):
-        acc = F64(0.0)
-        for g in range(G):
-            acc = acc + C[m * G + g]
-        flags[m] = 1 if (acc / F64(G)) < F64(F32(tau)) else 0
+        acc = F64(C[m * G])
+        for g in range(1, G):
+            c = F64(C[m * G + g])
+            acc = acc + c if pooling == "mean" else (max(acc, c) if pooling == "max" else min(acc, c))
+        pooled = acc / F64(G) if pooling == "mean" else acc
+        flags[m] = 1 if pooled < F64(F32(tau)) else 0
     return flags
 
 
@@ -232,13 +284,15 @@ class FreeKVOracle:
     """State of one (layer, request) and the decode step on it."""
 
     def __init__(self, n_q: int, n_kv: int, d: int, p: int, budget: int, sink: int,
-                 window: int, tau: float, max_ctx: int):
+                 window: int, tau: float, max_ctx: int, select_pooling: str = "MeanS",
+                 corr_pooling: str = "mean"):
         assert n_q % n_kv == 0 and budget % p == 0 and sink % p == 0 and window % p == 0
         self.n_q, self.n_kv, self.d, self.p = n_q, n_kv, d, p
         self.G = n_q // n_kv
         self.budget, self.sink, self.window, self.tau = budget, sink, window, tau
         self.k = (budget - sink - window) // p
         self.max_ctx = max_ctx
+        self.select_pooling, self.corr_pooling = select_pooling, corr_pooling
         max_pages = (max_ctx + p - 1) // p
         self.K = np.zeros((max_ctx, n_kv, d), dtype=F32)
         self.V = np.zeros((max_ctx, n_kv, d), dtype=F32)
@@ -288,8 +342,10 @@ class FreeKVOracle:
         """Sel(q): page ids per KV head [n_kv, k] (ascending, -1 padded), with the weights and scores it used."""
         g = self.geom()
         lo, hi = g.cand_lo, g.cand_lo + g.n_cand
+        if self.select_pooling in ("MeanQ", "MaxQ"):
+            q = pool_queries(q, self.G, self.select_pooling)      # one pooled query per KV head
         P = page_weights(q, self.kmax[lo:hi], self.kmin[lo:hi])
-        score = pooled_scores(P, self.G)
+        score = pooled_scores(P, self.G, self.select_pooling)
         ids = np.full((self.n_kv, self.k), -1, dtype=np.int32)
         for m in range(self.n_kv):
             top = topk_pages(score[m], g.k_eff)
@@ -333,7 +389,7 @@ class FreeKVOracle:
             flags = np.ones(self.n_kv, dtype=np.uint8)
         else:
             C = query_cosine(q, self.q_prev)
-            flags = correction_flags(C, self.G, self.tau)
+            flags = correction_flags(C, self.G, self.tau, self.corr_pooling)
         used = np.where(flags[:, None] != 0, new_ids, self.active)
         out = self.attend(q, used)
         # pages of Sel(q_i) not in the GPU cache of selected pages: those of the

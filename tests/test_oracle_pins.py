@@ -425,3 +425,80 @@ def test_generator_statistics_and_determinism():
         lib = torch.from_numpy(x).to(tdt).view(torch.int16).numpy().view(np.uint16)
         np.testing.assert_array_equal(W.encode(x, name), lib)
         np.testing.assert_array_equal(W.decode(lib, name), torch.from_numpy(x).to(tdt).float().numpy())
+
+
+# ---------------------------------------------------------------- App. B.2 / B.3: alternative poolings
+def test_every_pooling_of_a_group_of_one_ranks_like_the_weights():
+    """With G = 1 pooling over the group is the identity: all six variants must pick argsort(P)."""
+    rng = np.random.default_rng(21)
+    o = {}
+    K = _rand_T(rng, (160, 2, 128)); V = _rand_T(rng, (160, 2, 128)); q = _rand_T(rng, (2, 128))
+    for pooling in O.SELECT_POOLINGS:
+        orc = O.FreeKVOracle(2, 2, 128, 4, 24, 4, 8, 0.8, 256, select_pooling=pooling)
+        orc.load_prefix(K, V)
+        ids, P, score = orc.select(q)
+        for m in range(2):
+            best = sorted(np.argsort(-P[m].astype(np.float64), kind="stable")[:3] + orc.geom().cand_lo)
+            assert ids[m].tolist() == best, pooling
+        o[pooling] = ids
+    for pooling in O.SELECT_POOLINGS:
+        np.testing.assert_array_equal(o[pooling], o["MeanS"])
+
+
+def test_pooled_scores_variants_against_direct_formulas():
+    rng = np.random.default_rng(22)
+    G, n_kv, n = 4, 2, 97
+    P = (rng.standard_normal((G * n_kv, n)) * 2).astype(np.float32)
+    P64 = P.astype(np.float64)
+    sm = np.exp(P64 - P64.max(axis=1, keepdims=True)); sm /= sm.sum(axis=1, keepdims=True)
+    grp = lambda x: x.reshape(n_kv, G, n)
+    np.testing.assert_allclose(O.pooled_scores(P, G, "MaxS"), grp(sm).max(axis=1), rtol=3e-6, atol=1e-9)
+    np.testing.assert_allclose(O.pooled_scores(P, G, "MeanS"), grp(sm).mean(axis=1), rtol=3e-6, atol=1e-9)
+    np.testing.assert_allclose(O.pooled_scores(P, G, "MeanQK"), grp(P64).mean(axis=1), rtol=1e-6, atol=1e-6)
+    np.testing.assert_array_equal(O.pooled_scores(P, G, "MaxQK"), grp(P).max(axis=1))
+    # the variants really differ: one head loves page 0, three heads mildly prefer page 1
+    Q = np.array([[9.0, 0.0, 0.0], [0.0, 2.0, 0.0], [0.0, 2.0, 0.0], [0.0, 2.0, 0.0]], dtype=np.float32)
+    assert np.argmax(O.pooled_scores(Q, 4, "MaxS")[0]) == 0 and np.argmax(O.pooled_scores(Q, 4, "MaxQK")[0]) == 0
+    assert np.argmax(O.pooled_scores(Q, 4, "MeanS")[0]) == 1
+    Q2 = np.array([[5.0, 0.0, 0.0], [0.0, 2.0, 0.0], [0.0, 2.0, 0.0], [0.0, 2.0, 0.0]], dtype=np.float32)
+    assert np.argmax(O.pooled_scores(Q2, 4, "MeanQK")[0]) == 1 and np.argmax(O.pooled_scores(Q2, 4, "MaxQK")[0]) == 0
+
+
+def test_pooled_queries_and_their_page_weights():
+    rng = np.random.default_rng(23)
+    q = _rand_T(rng, (6, 128))
+    np.testing.assert_allclose(O.pool_queries(q, 3, "MeanQ"), q.reshape(2, 3, 128).astype(np.float64).mean(axis=1), rtol=1e-6, atol=1e-7)
+    np.testing.assert_array_equal(O.pool_queries(q, 3, "MaxQ"), q.reshape(2, 3, 128).max(axis=1))
+    # the weight of the pooled query still bounds every token logit of that pooled query
+    K = _rand_T(rng, (64, 2, 128))
+    kmax, kmin = O.page_summaries(K, 8)
+    for pooling in ("MeanQ", "MaxQ"):
+        qp = O.pool_queries(q, 3, pooling)
+        P = O.page_weights(qp, kmax, kmin)
+        assert P.shape == (2, 8)
+        for m in range(2):
+            logits = K[:, m, :].astype(np.float64) @ qp[m].astype(np.float64) / math.sqrt(128)
+            for j in range(8):
+                assert P[m, j] >= logits[j * 8:(j + 1) * 8].max() - 1e-4
+        np.testing.assert_array_equal(O.pooled_scores(P, 3, pooling), P)
+
+
+def test_correction_pooling_variants():
+    C = np.array([0.95, 0.6, 0.9, 0.9])
+    np.testing.assert_array_equal(O.correction_flags(C, 2, 0.8, "mean"), [1, 0])     # 0.775 < 0.8
+    np.testing.assert_array_equal(O.correction_flags(C, 2, 0.8, "max"), [0, 0])      # 0.95 is not
+    np.testing.assert_array_equal(O.correction_flags(C, 2, 0.8, "min"), [1, 0])      # 0.6 is
+    np.testing.assert_array_equal(O.correction_flags(np.array([0.7, 0.75]), 2, 0.8, "max"), [1])
+    np.testing.assert_array_equal(O.correction_flags(np.array([0.85, 0.95]), 2, 0.8, "min"), [0])
+
+
+@pytest.mark.parametrize("pooling", ["MaxS", "MeanQK", "MaxQK", "MeanQ", "MaxQ"])
+def test_variants_with_budget_covering_context_are_dense_attention(pooling):
+    rng = np.random.default_rng(24)
+    o = O.FreeKVOracle(6, 2, 128, 4, 64, 4, 8, 1.5, 64, select_pooling=pooling)
+    K = _rand_T(rng, (50, 2, 128)); V = _rand_T(rng, (50, 2, 128))
+    o.load_prefix(K, V)
+    q = _rand_T(rng, (6, 128)); kn = _rand_T(rng, (2, 128)); vn = _rand_T(rng, (2, 128))
+    res = o.step(q, kn, vn)
+    dense = O.dense_attention(q, np.concatenate([K, kn[None]]), np.concatenate([V, vn[None]]))
+    np.testing.assert_allclose(res["out"], dense, rtol=1e-12, atol=1e-13)
