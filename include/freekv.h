@@ -58,6 +58,22 @@ extern "C" {
 #define FKV_RECALL_MEMCPY  1  /* one hipMemcpyAsync per 16 KiB unit on the copy stream; the miss
                                  list is first copied to the host and the call BLOCKS on it      */
 
+/* Pooling of the page selection over the G query heads of a KV head (App. B.2).  MEAN_S is
+ * the method (Sec. 3.2): mean of the per-head softmax over the candidate pages.  MAX_S: their
+ * maximum.  MEAN_QK / MAX_QK: mean / maximum of the page weights themselves.  MEAN_Q / MAX_Q:
+ * page weights of the channel-wise mean / maximum query of the group. */
+#define FKV_POOL_MEAN_S   0
+#define FKV_POOL_MAX_S    1
+#define FKV_POOL_MEAN_QK  2
+#define FKV_POOL_MAX_QK   3
+#define FKV_POOL_MEAN_Q   4
+#define FKV_POOL_MAX_Q    5
+/* Pooling of the query similarity C_i over the group before the test against tau (Sec. 3.3;
+ * alternatives of App. B.3): mean (the method), maximum, minimum. */
+#define FKV_CORR_MEAN  0
+#define FKV_CORR_MAX   1
+#define FKV_CORR_MIN   2
+
 /* which page list sparse attention reads */
 #define FKV_USE_ACTIVE   0  /* pages committed at the previous step (reuse)        */
 #define FKV_USE_PENDING  1  /* pages picked at this step                           */
@@ -85,6 +101,8 @@ typedef struct {
   int32_t placement;       /* FKV_PLACE_*                                           */
   float   tau;             /* correction threshold; <= -1 never corrects, > 1 always */
   int32_t recall_mode;     /* FKV_RECALL_* (placement HOST)                         */
+  int32_t select_pooling;  /* FKV_POOL_*: how the selection is pooled over a GQA group */
+  int32_t corr_pooling;    /* FKV_CORR_*: how the query similarity is pooled over it   */
 } fkv_config;
 
 /* Bytes the library needs: a device arena, and (placement HOST) a pinned,

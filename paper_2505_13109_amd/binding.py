@@ -30,13 +30,18 @@ class FreeKVError(RuntimeError):
     pass
 
 
+# names of the FKV_POOL_* / FKV_CORR_* codes, in code order
+SELECT_POOLINGS = ("MeanS", "MaxS", "MeanQK", "MaxQK", "MeanQ", "MaxQ")
+CORR_POOLINGS = ("mean", "max", "min")
+
+
 class FkvConfig(C.Structure):
     _fields_ = [
         ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
         ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
         ("max_ctx", C.c_int32), ("budget_tokens", C.c_int32), ("sink_tokens", C.c_int32),
         ("window_tokens", C.c_int32), ("dtype", C.c_int32), ("placement", C.c_int32),
-        ("tau", C.c_float), ("recall_mode", C.c_int32),
+        ("tau", C.c_float), ("recall_mode", C.c_int32), ("select_pooling", C.c_int32), ("corr_pooling", C.c_int32),
     ]
 
 
@@ -104,12 +109,13 @@ class FreeKV:
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, max_ctx, budget, sink, window,
                  tau, dtype="bf16", placement=FKV_PLACE_HBM, head_dim=128, page_size=32, device="cuda:0",
-                 recall_mode=0):
+                 recall_mode=0, select_pooling="MeanS", corr_pooling="mean"):
         import torch
         self._torch = torch
         self.L = lib()
         self.cfg = FkvConfig(n_layers, batch, n_q_heads, n_kv_heads, head_dim, page_size, max_ctx,
-                             budget, sink, window, {"fp16": 0, "bf16": 1}[dtype], placement, tau, recall_mode)
+                             budget, sink, window, {"fp16": 0, "bf16": 1}[dtype], placement, tau, recall_mode,
+                             SELECT_POOLINGS.index(select_pooling), CORR_POOLINGS.index(corr_pooling))
         self.dtype = dtype
         self.torch_dtype = torch.float16 if dtype == "fp16" else torch.bfloat16
         self.k = (budget - sink - window) // page_size

@@ -94,6 +94,8 @@ const char* check_config(const fkv_config* c) {
   if ((c->budget_tokens - c->sink_tokens - c->window_tokens) / PG > 1024) return "more than 1024 selectable pages are not supported";
   if (c->tau != c->tau) return "tau is NaN";
   if (c->recall_mode != FKV_RECALL_GATHER && c->recall_mode != FKV_RECALL_MEMCPY) return "bad recall_mode";
+  if (c->select_pooling < FKV_POOL_MEAN_S || c->select_pooling > FKV_POOL_MAX_Q) return "bad select_pooling";
+  if (c->corr_pooling < FKV_CORR_MEAN || c->corr_pooling > FKV_CORR_MIN) return "bad corr_pooling";
   return nullptr;
 }
 
@@ -294,7 +296,8 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
     v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeSharedMemPerBlockOptin, dev_id) == hipSuccess && v > max_lds) max_lds = v;
   }
-  ctx->dims = Dims{cfg->batch, cfg->n_q_heads, cfg->n_kv_heads, cfg->n_q_heads / cfg->n_kv_heads, l.k, l.max_pages, cfg->dtype, max_lds};
+  ctx->dims = Dims{cfg->batch, cfg->n_q_heads, cfg->n_kv_heads, cfg->n_q_heads / cfg->n_kv_heads, l.k, l.max_pages, cfg->dtype, max_lds,
+                   cfg->select_pooling, cfg->corr_pooling};
   ctx->dev = static_cast<char*>(dev_arena);
   ctx->host = cfg->placement == FKV_PLACE_HOST ? static_cast<char*>(host_arena) : nullptr;
   ctx->layers.resize(cfg->n_layers);

@@ -82,6 +82,7 @@ struct AttnArgs {
   const uint16_t* q_prev;
   int have_prev;
   float tau;
+  int corr_pool;
   const uint16_t* k_new;
   const uint16_t* v_new;
   const int* sel_done;       // [heads]: epoch of the last finished selection
@@ -162,11 +163,7 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
         if (lane == 0) s_cos[gg] = c;
       }
       __syncthreads();
-      if (threadIdx.x == 0) {
-        double acc = 0.0;
-        for (int gg = 0; gg < G; ++gg) acc = acc + s_cos[gg];
-        s_flag = (acc / (double)G) < (double)a.tau ? 1 : 0;
-      }
+      if (threadIdx.x == 0) s_flag = pooled_flag(s_cos, G, a.tau, a.corr_pool);
       __syncthreads();
       pending = s_flag != 0;
     } else {

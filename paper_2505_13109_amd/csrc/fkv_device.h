@@ -35,6 +35,21 @@ __device__ __forceinline__ size_t summ_idx(int b, int m, int n_kv, int which, in
   return ((size_t)((b * n_kv + m) * 2 + which) * max_pages + page) * D;
 }
 
+// correction flag of a KV head from the similarities of its G query heads (Sec. 3.3): the
+// group-pooled similarity strictly below tau.  pool: 0 mean (sum in head order / G), 1 maximum,
+// 2 minimum (App. B.3).  fp64, one thread.
+__device__ __forceinline__ int pooled_flag(const double* c, int G, float tau, int pool) {
+  double acc = c[0];
+  for (int gg = 1; gg < G; ++gg) {
+    const double v = c[gg];
+    if (pool == 0) acc = acc + v;
+    else if (pool == 1) acc = v > acc ? v : acc;
+    else acc = v < acc ? v : acc;
+  }
+  if (pool == 0) acc = acc / (double)G;
+  return acc < (double)tau ? 1 : 0;
+}
+
 // cosine of one query head against the previous step's query (Sec. 3.1); one wave, fp64
 template <int DT>
 __device__ __forceinline__ double head_cosine(const uint16_t* q, const uint16_t* q_prev, int lane, uint32_t* q_word) {

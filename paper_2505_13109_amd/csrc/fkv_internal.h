@@ -51,7 +51,7 @@ __host__ __device__ inline int v_elem_off(int t, int ch) {
 }
 
 // ---- launch wrappers (defined in the kernel files) ----------------------
-struct Dims { int batch, n_q, n_kv, G, k, max_pages, dtype, max_lds; };
+struct Dims { int batch, n_q, n_kv, G, k, max_pages, dtype, max_lds, sel_pool, corr_pool; };
 
 // the fused step kernel: roles are OR-ed
 constexpr int ROLE_APPEND = 1, ROLE_CORR = 2, ROLE_SELECT = 4;

@@ -86,6 +86,7 @@ static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, i
   a.g = g;
   a.pd = io.pd; a.summ = io.summ; a.k_new = io.k_new; a.v_new = io.v_new;
   a.q = io.q; a.q_prev = io.q_prev; a.q_stage = io.q_stage; a.have_prev = io.have_prev; a.tau = io.tau;
+  a.corr_pool = d.corr_pool; a.sel_pool = d.sel_pool;
   a.flags = io.flags; a.flags_user = io.flags_user; a.cosine = io.cosine;
   a.P = io.P; a.score = io.score; a.ids = io.ids; a.ids_user = io.ids_user; a.counters = io.counters; a.tstamp = io.tstamp;
   const int heads = d.batch * d.n_kv;
@@ -194,7 +195,7 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     at.n_splits = (n_att + at.pps - 1) / at.pps;
     at.counters = lio.attn_counters; at.out = lio.out; at.g = g;
     at.n_q = d.n_q; at.n_kv = d.n_kv; at.G = d.G; at.k = d.k; at.tstamp = io.tstamp;
-    at.fused = 1; at.q_prev = io.q_prev; at.have_prev = io.have_prev; at.tau = io.tau;
+    at.fused = 1; at.q_prev = io.q_prev; at.have_prev = io.have_prev; at.tau = io.tau; at.corr_pool = d.corr_pool;
     at.k_new = io.k_new; at.v_new = io.v_new; at.sel_done = lio.sel_done; at.epoch = lio.epoch; at.status = lio.status;
     a.attn_block0 = grid;
     grid += heads * at.n_splits;

@@ -15,7 +15,10 @@
 //            degree-6 Horner in f with separate multiply and add; ldexp(., n);
 //            0 below t < -64; E = rint(e * 2^31) as integer; Z = integer sum of E;
 //   pooling: fl32( (sum_g fp64(E_g) / fp64(Z_g), g ascending) / fp64(G) );
-//   top-k:   radix select on the fp32 bit pattern, ties to the lower page id.
+//            (alternatives, App. B.2: fl32(max_g E_g / Z_g); the fp32 sum of the weights in head
+//            order divided by G, or their maximum; the weight of the group's mean or maximum query)
+//   top-k:   radix select on the order-preserving image of the fp32 bit pattern, ties to the
+//            lower page id.
 #pragma once
 #include "fkv_device.h"
 
@@ -51,10 +54,12 @@ struct StepArgs {
   uint16_t* q_stage;
   int have_prev;
   float tau;
+  int corr_pool;             // FKV_CORR_*
   uint8_t* flags;
   uint8_t* flags_user;
   double* cosine;
   // selection
+  int sel_pool;              // FKV_POOL_*
   float* P;
   float* score;
   int32_t* ids;
@@ -116,11 +121,7 @@ __device__ __forceinline__ void corr_role(const StepArgs& a, int head) {
   __syncthreads();
   if (threadIdx.x == 0) {
     uint8_t f = 1;
-    if (a.have_prev) {
-      double acc = 0.0;
-      for (int gg = 0; gg < G; ++gg) acc = acc + cg[gg];
-      f = (acc / (double)G) < (double)a.tau ? 1 : 0;
-    }
+    if (a.have_prev) f = (uint8_t)pooled_flag(cg, G, a.tau, a.corr_pool);
     a.flags[head] = f;
     if (a.flags_user) a.flags_user[head] = f;
   }
@@ -158,6 +159,20 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
     const uint4 wq = *reinterpret_cast<const uint4*>(a.q + (size_t)(b * a.n_q + m * G + gg) * D + c8 * 8);
     unpack8<DT>(wq, f[gg]);
   }
+  // Variants that pool the QUERY over the group (App. B.2, MeanQ / MaxQ): one pooled query per KV
+  // head takes the place of head 0 of the group, and only its row of P is written.
+  const bool qmode = a.sel_pool >= 4;
+  if (qmode) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      float acc = f[0][c];
+#pragma unroll
+      for (int gg = 1; gg < G; ++gg) acc = a.sel_pool == 4 ? acc + f[gg][c] : fmaxf(acc, f[gg][c]);
+      // fp32 quotient by way of fp64: correctly rounded (53 >= 2 * 24 + 2 bits)
+      if (a.sel_pool == 4) acc = (float)((double)acc / (double)G);
+      f[0][c] = acc;
+    }
+  }
   const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
 #pragma unroll
   for (int ps = 0; ps < SCORE_PASSES; ++ps) {
@@ -167,11 +182,23 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
     unpack8<DT>(wmin[ps], kn);
 #pragma unroll
     for (int gg = 0; gg < G; ++gg) {
-      // chunk sum, left to right.  The product q_c * (q_c >= 0 ? kmax_c : kmin_c) is exact in
-      // fp32, so the fma rounds once, exactly like "s + product".
-      float s = 0.0f;
+      if (qmode && gg > 0) break;
+      // chunk sum, left to right.  The product q_c * (q_c >= 0 ? kmax_c : kmin_c) of two 16-bit
+      // floats is exact in fp32, so the fma rounds once, exactly like "s + product"; a mean
+      // query is a full fp32 number, so there the product is rounded on its own first.
+      float s;
+      if (qmode) {
+        s = f[0][0] * (f[0][0] >= 0.0f ? kx[0] : kn[0]);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) s = __builtin_fmaf(f[gg][c], f[gg][c] >= 0.0f ? kx[c] : kn[c], s);
+        for (int c = 1; c < 8; ++c) {
+          const float pr = f[0][c] * (f[0][c] >= 0.0f ? kx[c] : kn[c]);
+          s = s + pr;
+        }
+      } else {
+        s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s = __builtin_fmaf(f[gg][c], f[gg][c] >= 0.0f ? kx[c] : kn[c], s);
+      }
       // adjacent-pair tree over the 16 chunk sums (xor 1, 2 in quads; the mirrors pair lanes
       // that hold equal partial sums' complements, which is the same tree)
       s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0xB1, 0xf, 0xf, false));
@@ -204,6 +231,16 @@ __device__ __forceinline__ uint32_t softmax_fixed(float p, float mx) {
   return (uint32_t)__builtin_rintf(e * 2147483648.0f);
 }
 
+// Scores can be negative in the variants that pool the weights themselves: map the fp32 bit
+// pattern to an unsigned key with the same order (-0 counts as +0), and back.
+__device__ __forceinline__ uint32_t score_key(float sc) {
+  const uint32_t u = __float_as_uint(sc + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_score(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
 template <int G, bool STAGED>
 __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32_t* key) {
   __shared__ float s_redf[STEP_WAVES][G];
@@ -228,6 +265,9 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
   uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
   constexpr bool staged = STAGED;                      // else: re-read the weights from memory in each pass
+  const int mode = a.sel_pool;                         // FKV_POOL_*
+  const bool soft = mode <= 1;                         // the variants that pool softmax values
+  const int ng = mode >= 4 ? 1 : G;                    // rows of P in use (pooled query: the group's first)
 #pragma unroll
   for (int p = 0; p < 4; ++p)
     if (tid < 256) hist[p][tid] = 0;
@@ -237,22 +277,24 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   float mx[G];
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) mx[gg] = -__builtin_inff();
-  for (int j0 = tid; j0 < n; j0 += 8 * STEP_THREADS) {
-    float v[8][G];
+  if (soft || staged) {
+    for (int j0 = tid; j0 < n; j0 += 8 * STEP_THREADS) {
+      float v[8][G];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = min(j0 + u * STEP_THREADS, n - 1);
+      for (int u = 0; u < 8; ++u) {
+        const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
-      for (int gg = 0; gg < G; ++gg) v[u][gg] = ld_dev(Pm + (size_t)gg * a.max_pages + j);
-    }
+        for (int gg = 0; gg < G; ++gg) v[u][gg] = gg < ng ? ld_dev(Pm + (size_t)gg * a.max_pages + j) : 0.0f;
+      }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = j0 + u * STEP_THREADS;
-      if (j < n) {
+      for (int u = 0; u < 8; ++u) {
+        const int j = j0 + u * STEP_THREADS;
+        if (j < n) {
 #pragma unroll
-        for (int gg = 0; gg < G; ++gg) {
-          if (staged) pw[gg * n + j] = __float_as_uint(v[u][gg]);
-          mx[gg] = fmaxf(mx[gg], v[u][gg]);
+          for (int gg = 0; gg < G; ++gg) {
+            if (staged) pw[gg * n + j] = __float_as_uint(v[u][gg]);
+            mx[gg] = fmaxf(mx[gg], v[u][gg]);
+          }
         }
       }
     }
@@ -274,7 +316,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   unsigned long long z[G];
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) z[gg] = 0;
-  for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {   // 4 x G independent chains per trip
+  for (int j0 = tid; soft && j0 < n; j0 += 4 * STEP_THREADS) {   // 4 x G independent chains per trip
     float v[4][G];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -313,22 +355,44 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   // pooled score of each candidate (each thread reads back only what it wrote); the top
   // byte of its key goes straight into the first histogram
   for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {
-    uint32_t e[4][G];
+    uint32_t e[4][G];                                // softmax numerators, or the bits of the weights
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
-      for (int gg = 0; gg < G; ++gg)
-        e[u][gg] = staged ? pw[gg * n + j] : softmax_fixed(ld_dev(Pm + (size_t)gg * a.max_pages + j), mx[gg]);
+      for (int gg = 0; gg < G; ++gg) {
+        if (staged) e[u][gg] = pw[gg * n + j];
+        else if (gg < ng) {
+          const float w = ld_dev(Pm + (size_t)gg * a.max_pages + j);
+          e[u][gg] = soft ? softmax_fixed(w, mx[gg]) : __float_as_uint(w);
+        } else e[u][gg] = 0;
+      }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int j = j0 + u * STEP_THREADS;
-      double acc = 0.0;
+      float sc;
+      if (soft) {
+        // mean (the method) or maximum over the group of the softmax values, in fp64
+        double acc = (double)e[u][0] / zd[0];
 #pragma unroll
-      for (int gg = 0; gg < G; ++gg) acc = acc + (double)e[u][gg] / zd[gg];
-      const float sc = (float)(acc / (double)G);
-      const uint32_t kj = __float_as_uint(sc);       // sc >= 0: bit patterns order like the values
+        for (int gg = 1; gg < G; ++gg) {
+          const double sg = (double)e[u][gg] / zd[gg];
+          if (mode == 0) acc = acc + sg;
+          else acc = sg > acc ? sg : acc;
+        }
+        sc = mode == 0 ? (float)(acc / (double)G) : (float)acc;
+      } else {
+        // mean or maximum of the weights themselves in fp32, head order; or the pooled query's weight
+        float acc = __uint_as_float(e[u][0]);
+#pragma unroll
+        for (int gg = 1; gg < G; ++gg) {
+          if (mode == 2) acc = acc + __uint_as_float(e[u][gg]);
+          else if (mode == 3) acc = fmaxf(acc, __uint_as_float(e[u][gg]));
+        }
+        sc = mode == 2 ? (float)((double)acc / (double)G) : acc;
+      }
+      const uint32_t kj = score_key(sc);
       if (j < n) {
         key[j] = kj;
         atomicAdd(&hist[3][kj >> 24], 1u);
@@ -401,7 +465,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     if (outu) outu[i] = -1;
   }
   for (int j = tid; j < n; j += STEP_THREADS)          // pooled scores, kept for inspection
-    a.score[(size_t)head * a.max_pages + lo + j] = __uint_as_float(key[j]);
+    a.score[(size_t)head * a.max_pages + lo + j] = key_score(key[j]);
 }
 
 

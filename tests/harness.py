@@ -33,7 +33,8 @@ def _diff(got, ref):
 class Pair:
     """One HIP context and the matching oracles for `layers` x `batch` of a workload."""
 
-    def __init__(self, wl, layers, ctx=None, placement=None, tau=None, max_ctx=None, steps=None, recall_mode=0):
+    def __init__(self, wl, layers, ctx=None, placement=None, tau=None, max_ctx=None, steps=None, recall_mode=0,
+                 select_pooling="MeanS", corr_pooling="mean"):
         self.wl = wl
         self.layers = list(layers)
         self.n_ctx = wl.ctx if ctx is None else ctx
@@ -45,7 +46,9 @@ class Pair:
         self.g = fkv.FreeKV(n_layers=len(self.layers), batch=wl.batch, n_q_heads=wl.n_q_heads,
                             n_kv_heads=wl.n_kv_heads, max_ctx=self.max_ctx, budget=wl.budget,
                             sink=wl.sink, window=wl.window, tau=self.tau, dtype=wl.dtype,
-                            placement=self.placement, recall_mode=recall_mode)
+                            placement=self.placement, recall_mode=recall_mode,
+                            select_pooling=select_pooling, corr_pooling=corr_pooling)
+        self.q_pooled = select_pooling in ("MeanQ", "MaxQ")
         self.oracles = {}
         self.q, self.kd, self.vd = {}, {}, {}
         self.copy_stream = torch.cuda.Stream()
@@ -54,7 +57,8 @@ class Pair:
             for r in range(wl.batch):
                 (K, Kb), (V, Vb) = W.kv_prefix(wl, layer, r, self.n_ctx)
                 o = O.FreeKVOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, p, wl.budget, wl.sink,
-                                   wl.window, self.tau, self.max_ctx)
+                                   wl.window, self.tau, self.max_ctx,
+                                   select_pooling=select_pooling, corr_pooling=corr_pooling)
                 o.load_prefix_bulk(K, V)
                 self.oracles[(li, r)] = o
                 Kb_all.append(Kb)
@@ -108,7 +112,9 @@ class Pair:
             tag = f"layer {self.layers[li]} step {t} request {r} L {gm.L}"
             if deep and wl.k_pages > 0:      # with nothing selectable the library skips scoring altogether
                 lo, hi = gm.cand_lo, gm.cand_lo + gm.n_cand
-                assert np.array_equal(Pw[r, :, lo:hi], ref["P"]), f"page weights differ: {tag}: {_diff(Pw[r, :, lo:hi], ref['P'])}"
+                # a pooled query has one row of weights per KV head, kept in the row of the group's first head
+                Pg = Pw[r, ::wl.n_q_heads // wl.n_kv_heads, lo:hi] if self.q_pooled else Pw[r, :, lo:hi]
+                assert np.array_equal(Pg, ref["P"]), f"page weights differ: {tag}: {_diff(Pg, ref['P'])}"
                 assert np.array_equal(Sc[r, :, lo:hi], ref["score"]), f"pooled scores differ: {tag}: {_diff(Sc[r, :, lo:hi], ref['score'])}"
                 if t > 0:
                     np.testing.assert_allclose(cosv[r], ref["cosine"], rtol=0, atol=1e-12, err_msg=tag)

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 def _cfg(**kw):
     base = dict(n_layers=2, batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, page_size=32,
                 max_ctx=4096, budget_tokens=512, sink_tokens=32, window_tokens=32, dtype=1,
-                placement=0, tau=0.8, recall_mode=0)
+                placement=0, tau=0.8, recall_mode=0, select_pooling=0, corr_pooling=0)
     base.update(kw)
     return FkvConfig(**base)
 
@@ -47,7 +47,8 @@ def test_arena_bytes_and_config_checks():
     assert dev.value >= 2 * 8 * gpu_units * 16384 and dev.value < store
     for bad in (dict(head_dim=64), dict(page_size=16), dict(n_q_heads=30), dict(n_q_heads=128),
                 dict(max_ctx=100), dict(budget_tokens=48), dict(dtype=3), dict(placement=2),
-                dict(sink_tokens=40), dict(n_layers=0), dict(recall_mode=7)):
+                dict(sink_tokens=40), dict(n_layers=0), dict(recall_mode=7), dict(select_pooling=6),
+                dict(select_pooling=-1), dict(corr_pooling=3)):
         assert L.fkv_arena_bytes(C.byref(_cfg(**bad)), C.byref(dev), C.byref(host)) == -1, bad
         assert L.fkv_last_error(None)
 

@@ -202,3 +202,69 @@ def test_host_pool_recall_with_memcpy_per_unit():
     pr.check_cached_pages(0, 1, 2, where=2)
     assert pr.stats["misses"] > 0
     pr.close()
+
+
+# ---------------------------------------------------------------- App. B.2 / B.3: the alternative poolings
+VARIANTS = ["MaxS", "MeanQK", "MaxQK", "MeanQ", "MaxQ"]
+
+
+@pytest.mark.parametrize("pooling", VARIANTS)
+def test_selection_pooling_variants(pooling):
+    """Each alternative group pooling of the selection, every step compared, G = 4 bf16 and G = 7 fp16."""
+    for wl in (W.Workload("v4", 1, 1, 16, 4, "bf16", 6000, 512, 32, 64, 0.8, 24, 0.8, 0.6, 31, shift_every=9),
+               W.Workload("v7", 1, 2, 14, 2, "fp16", 20, 256, 32, 64, 0.75, 200, 0.75, 0.7, 32, shift_every=60)):
+        pr = _pair(wl, [1], select_pooling=pooling)
+        for t in range(wl.steps):
+            pr.step(0, t)
+        assert 0 < pr.stats["flagged"] < pr.stats["heads"]
+        print(pooling, wl.name, pr.stats)
+        pr.close()
+
+
+@pytest.mark.parametrize("pooling", ["max", "min"])
+def test_correction_pooling_variants(pooling):
+    """Max- and min-pooled query similarity decide the flags; both sides must flag the same heads."""
+    wl = W.Workload("cp", 1, 1, 12, 3, "bf16", 3000, 512, 32, 64, 0.72, 120, 0.72, 0.7, 33, shift_every=40)
+    counts = {}
+    for cp in ("mean", pooling):
+        pr = _pair(wl, [2], corr_pooling=cp)
+        for t in range(wl.steps):
+            pr.step(0, t, deep=(t % 8 == 0))
+        counts[cp] = pr.stats["flagged"]
+        assert 0 < counts[cp] < pr.stats["heads"]
+        pr.close()
+    # the largest similarity of a group is below tau less often than the mean, the smallest more often
+    assert counts["max"] < counts["mean"] if pooling == "max" else counts["min"] > counts["mean"]
+    print("corr pooling", counts)
+
+
+@pytest.mark.parametrize("pooling", ["MeanS"] + VARIANTS)
+def test_negative_page_weights_and_long_context_selection(pooling):
+    """With all-negative queries a page of all-positive keys has a negative weight and one of all-negative
+    keys a positive one; only 20 pages are of the second kind, so most of the k = 62 picks are decided
+    among negative scores (the variants that rank raw weights).  150K tokens with G = 8 is past what
+    the selection can stage in LDS next to its keys."""
+    import paper_2505_13109_amd as fkv
+    from harness import to_dev
+    rng = np.random.default_rng(77)
+    n_ctx, n_q, n_kv = 150000, 16, 2
+    g = fkv.FreeKV(n_layers=1, batch=1, n_q_heads=n_q, n_kv_heads=n_kv, max_ctx=150016, budget=2048, sink=32,
+                   window=32, tau=0.8, dtype="bf16", select_pooling=pooling)
+    Kf = (np.abs(rng.standard_normal((n_ctx, n_kv, 128))) + 0.05).astype(np.float32)
+    for page in rng.choice(np.arange(10, 4600), 20, replace=False):
+        Kf[page * 32:(page + 1) * 32] *= -1.0
+    Kb = W.encode(Kf, "bf16")
+    K = W.decode(Kb, "bf16")
+    o = O.FreeKVOracle(n_q, n_kv, 128, 32, 2048, 32, 32, 0.8, 150016, select_pooling=pooling)
+    o.load_prefix_bulk(K, K)
+    g.load_prefix(0, to_dev(Kb[None], "bf16"), to_dev(Kb[None], "bf16"))
+    ids = torch.zeros((1, n_kv, g.k), dtype=torch.int32, device="cuda")
+    for trial in range(3):
+        qf = rng.standard_normal((n_q, 128))
+        qb = W.encode((qf if trial == 0 else -np.abs(qf) - 0.01).astype(np.float32), "bf16")
+        g.page_select(0, to_dev(qb[None], "bf16"), ids)
+        ref_ids, P, score = o.select(W.decode(qb, "bf16"))
+        if trial > 0 and pooling not in ("MeanS", "MaxS"):
+            assert (score > 0).any() and ((score > 0).sum(axis=1) < g.k).all()    # negative scores get picked
+        assert np.array_equal(ids.cpu().numpy()[0], ref_ids), (pooling, trial)
+    g.close()
