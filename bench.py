@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (stated in config.workload)")
     ap.add_argument("--recall-mode", type=int, default=0, help="placement 1: 0 gather kernel, 1 hipMemcpyAsync per unit")
     ap.add_argument("--placement", type=int, default=-1, help="override KV placement: 0 HBM, 1 pinned host pool")
+    ap.add_argument("--tau", type=float, default=None, help="override the correction threshold (stated in config.workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--standin-mb", type=int, default=0,
                     help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
@@ -124,6 +125,8 @@ def main():
         wl = wl.scaled(n_layers=args.layers)
     if args.placement >= 0:
         wl = wl.scaled(placement=args.placement)
+    if args.tau is not None:
+        wl = wl.scaled(tau=args.tau)
     if args.calibration_copy:
         a = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda:0")
         for _ in range(3):
@@ -199,6 +202,11 @@ def main():
     attn_ms, attn_n = ctx.profile_attn(q[n_steps - 1], out[0], max(1, K // 4), stream=stream)
 
     extra = {}
+    floor = {}
+    if one_launch:
+        # what a launch of that shape costs when its blocks return at once
+        f_ms, f_grid, f_lds = ctx.profile_launch_floor(0, 2048, stream=stream)
+        floor = {"empty_launch_same_shape_us": f_ms / 2048 * 1e3, "grid_blocks": f_grid, "dynamic_lds_bytes": f_lds}
     if wl.placement == 1:
         # page-cache misses of a few more (untimed) steps, read back per layer
         from paper_2505_13109_amd import binding as B
@@ -272,7 +280,7 @@ def main():
                      "algorithmic_bytes_per_launch": kern_b, "avg_launch_us": kern_s * 1e6,
                      "launches_timed": kern_n,
                      "standalone_attn_kernel_us": attn_ms / max(attn_n, 1) * 1e3,
-                     "event_pair_per_launch_us": pair_ms / max(pair_n, 1) * 1e3},
+                     "event_pair_per_launch_us": pair_ms / max(pair_n, 1) * 1e3, **floor},
     }
     ctx.close()
     if not args.no_cpu_baseline:

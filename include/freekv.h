@@ -198,6 +198,13 @@ int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches);
 int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, float* out_dev, int32_t reps,
                      void* stream, double* total_ms, int32_t* launches);
 
+/* The cost of a launch as such: `reps` launches, back to back on `stream` between one HIP event
+ * pair, of a kernel with the grid, block size and dynamic LDS of `layer`'s last one-launch
+ * layer-step whose blocks return at once.  FKV_ESTATE if that step took several launches.
+ * grid / lds_bytes (may be NULL) receive the shape.  Blocking. */
+int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* stream, double* total_ms,
+                             int32_t* grid, int32_t* lds_bytes);
+
 /* ---- introspection for tests (blocking: synchronises the device) --------- */
 #define FKV_DBG_SUMMARIES   0  /* T     [batch, n_kv, 2 (max,min), max_pages, d]      */
 #define FKV_DBG_WEIGHTS     1  /* f32   [batch, n_q, max_pages]  page weights P        */

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_step_launches",
+    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches",
 )
 
 
@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
         "fkv_profile_enable": (C.c_int, [vp, i32]),
         "fkv_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "fkv_profile_attn": (C.c_int, [vp, vp, sz, vp, i32, vp, C.POINTER(C.c_double), C.POINTER(i32)]),
+        "fkv_profile_launch_floor": (C.c_int, [vp, i32, i32, vp, C.POINTER(C.c_double), C.POINTER(i32), C.POINTER(i32)]),
         "fkv_debug_read": (C.c_int, [vp, i32, i32, vp, sz]),
         "fkv_debug_read_page": (C.c_int, [vp, i32, i32, i32, i32, i32, vp]),
     }
@@ -201,6 +202,13 @@ class FreeKV:
         ms, n = C.c_double(), C.c_int32()
         self._check(self.L.fkv_profile_read(self._h, C.byref(ms), C.byref(n)), "fkv_profile_read")
         return ms.value, n.value
+
+    def profile_launch_floor(self, layer, reps, stream=None):
+        """(ms for `reps` empty launches of the layer kernel's shape, grid, dynamic LDS bytes)"""
+        ms, grid, lds = C.c_double(), C.c_int32(), C.c_int32()
+        self._check(self.L.fkv_profile_launch_floor(self._h, layer, reps, _stream(stream), C.byref(ms),
+                                                    C.byref(grid), C.byref(lds)), "fkv_profile_launch_floor")
+        return ms.value, grid.value, lds.value
 
     def profile_attn(self, q_layers, out, reps, stream=None):
         """q_layers: [n_layers, batch, n_q, d] contiguous; returns (total_ms, launches)."""

@@ -27,6 +27,8 @@ struct LayerState {
   bool recall_outstanding = false;
   int epoch = 0;             // decode steps taken through the one-launch path (selection epochs)
   int last_launches = 0;     // kernel launches of the last fkv_decode_step (compute stream)
+  int last_grid = 0;         // grid and dynamic LDS of the last one-launch layer-step
+  size_t last_lds = 0;
   hipEvent_t ev_offload = nullptr;   // last page offload finished
   hipEvent_t ev_recall = nullptr;    // deferred recall into ACTIVE's slots finished
 };
@@ -528,6 +530,8 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     lio.sel_done = ctx->sel_done(layer);
     lio.epoch = ls.epoch + 1;
     lio.status = ctx->status(layer);
+    lio.launch_grid = &ls.last_grid;
+    lio.launch_lds = &ls.last_lds;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (ctx->prof_on && ctx->prof_used + 2 <= ctx->prof_ev.size()) {
       e0 = ctx->prof_ev[ctx->prof_used];
@@ -644,6 +648,34 @@ int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, flo
   if (rc) return rc;
   *total_ms = ms;
   *launches = n;
+  return FKV_OK;
+}
+
+int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* stream, double* total_ms,
+                             int32_t* grid, int32_t* lds_bytes) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!total_ms || reps < 1) return ctx->fail(FKV_EINVAL, "bad argument");
+  const LayerState& ls = ctx->layers[layer];
+  if (ls.last_launches != 1 || ls.last_grid < 1) return ctx->fail(FKV_ESTATE, "the layer's last step was not a single launch");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  FKV_HIP(ctx, hipEventCreate(&e0));
+  FKV_HIP(ctx, hipEventCreate(&e1));
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  if (!launch_floor(ls.last_grid, ls.last_lds, 4, st)) return ctx->fail(FKV_EHIP, "empty kernel refused its LDS size");
+  FKV_HIP(ctx, hipEventRecord(e0, st));
+  launch_floor(ls.last_grid, ls.last_lds, reps, st);
+  FKV_HIP(ctx, hipEventRecord(e1, st));
+  FKV_HIP(ctx, hipEventSynchronize(e1));
+  float ms = 0.f;
+  FKV_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  int rc = after_launch(ctx, "empty kernels");
+  if (rc) return rc;
+  *total_ms = ms;
+  if (grid) *grid = ls.last_grid;
+  if (lds_bytes) *lds_bytes = (int32_t)ls.last_lds;
   return FKV_OK;
 }
 

@@ -68,7 +68,10 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
 struct LayerIO {
   const int32_t* act_ids; float* part_o; float* part_ml; int max_splits; int* attn_counters; float* out;
   int* sel_done; int epoch; int* status;
+  int* launch_grid; size_t* launch_lds;      // out (may be null): shape of the launch that was made
 };
+// `reps` launches of a kernel that does nothing, with the given grid, 512 threads and dynamic LDS
+bool launch_floor(int grid, size_t lds, int reps, hipStream_t st);
 bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, hipStream_t st);
 int attn_pages_per_block(int n_att, int heads, int max_splits, int nw);
 void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint16_t* host_pool,

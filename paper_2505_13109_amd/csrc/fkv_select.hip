@@ -204,12 +204,36 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     fits = lds_fits_launch(lds, grid);
   }
   if (!fits) return false;                                 // big selections keep their own launches
+  if (lio.launch_grid) *lio.launch_grid = grid;
+  if (lio.launch_lds) *lio.launch_lds = lds;
   switch (d.G) {
 #define FKV_CASE(GG) case GG: return d.dtype == 0 ? launch_layer_g<0, GG>(a, grid, lds, st) : launch_layer_g<1, GG>(a, grid, lds, st);
     FKV_CASE(1) FKV_CASE(2) FKV_CASE(3) FKV_CASE(4) FKV_CASE(5) FKV_CASE(6) FKV_CASE(7) FKV_CASE(8)
 #undef FKV_CASE
     default: return false;
   }
+  return true;
+}
+
+// ---------------------------------------------------------------------------------
+// The cost of a launch as such: a kernel of the same shape whose blocks return at once.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(STEP_THREADS) void floor_kernel(uint32_t* sink) {
+  extern __shared__ uint32_t dyn_lds[];
+  if (sink) *sink = dyn_lds[0];             // never taken: keeps the LDS allocation in the kernel
+}
+
+bool launch_floor(int grid, size_t lds, int reps, hipStream_t st) {
+  static size_t granted = 48 * 1024;
+  if (lds > granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&floor_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    granted = lds;
+  }
+  for (int r = 0; r < reps; ++r) floor_kernel<<<grid, STEP_THREADS, lds, st>>>(nullptr);
   return true;
 }
 
