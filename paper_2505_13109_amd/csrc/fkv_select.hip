@@ -153,6 +153,8 @@ __global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
 }
 
 static bool g_no_layer_kernel = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '1'; }();
+// tuning knob for experiments: fewest passes a scoring block makes (default: chosen from the shape)
+static int g_min_passes = [] { const char* e = getenv("FKV_LAYER_PASSES"); return e ? atoi(e) : 0; }();
 
 template <int DT, int G>
 static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
@@ -175,10 +177,8 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
   LayerArgs a{};
   int grid = 0;
   size_t lds = 0;
-  bool fits = false;
-  // fewer, fatter scoring blocks if that is what lets every block of the launch carry the
-  // selection's LDS
-  for (int passes = 1; passes <= SCORE_PASSES && !fits; passes *= 2) {
+  // the launch with scoring blocks that make `passes` passes; does every block's LDS fit?
+  auto plan = [&](int passes) -> bool {
     size_t lds_staged, lds_keys;
     fill_step_args(d, roles, io, g, passes, a.s, grid, lds_staged, lds_keys);
     a.s.staged = lds_staged > lds_keys ? 1 : 0;
@@ -201,8 +201,20 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     grid += heads * at.n_splits;
     const size_t lds_attn = (size_t)STEP_WAVES * (32 + d.G * D) * sizeof(float);
     lds = lds_staged > lds_attn ? lds_staged : lds_attn;
-    fits = lds_fits_launch(lds, grid);
+    return lds_fits_launch(lds, grid);
+  };
+  // The kernel's registers allow one block per compute unit at a time.  Prefer the fewest passes
+  // per scoring block (most blocks) for which the whole launch is resident at once, so that no
+  // attention block queues behind the scoring blocks; if no choice gets there, the fewest passes
+  // whose LDS fits (fatter scoring blocks are also what lets big selections fit at all).
+  int chosen = 0;
+  for (int passes = g_min_passes > 0 ? g_min_passes : 1; passes <= SCORE_PASSES; passes *= 2) {
+    if (!plan(passes)) continue;
+    if (!chosen) chosen = passes;
+    if (g_min_passes > 0) break;
+    if (grid <= kComputeUnits) { chosen = passes; break; }
   }
+  const bool fits = chosen != 0 && plan(chosen);
   if (!fits) return false;                                 // big selections keep their own launches
   if (lio.launch_grid) *lio.launch_grid = grid;
   if (lio.launch_lds) *lio.launch_lds = lds;

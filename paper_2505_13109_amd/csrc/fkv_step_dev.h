@@ -241,6 +241,15 @@ __device__ __forceinline__ float key_score(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
+template <int U> struct UnrollBy { static constexpr int value = U; };
+
+// phase marks of the selection, kept in registers until its end (investigation builds only)
+#ifdef FKV_SEL_STAMPS
+#define FKV_SEL_MARK(i) const long long sel_t##i = wall_clock64()
+#else
+#define FKV_SEL_MARK(i)
+#endif
+
 template <int G, bool STAGED>
 __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32_t* key) {
   __shared__ float s_redf[STEP_WAVES][G];
@@ -262,6 +271,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     }
     return;
   }
+  FKV_SEL_MARK(0);
   const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
   uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
   constexpr bool staged = STAGED;                      // else: re-read the weights from memory in each pass
@@ -277,17 +287,21 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   float mx[G];
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) mx[gg] = -__builtin_inff();
-  if (soft || staged) {
-    for (int j0 = tid; j0 < n; j0 += 8 * STEP_THREADS) {
-      float v[8][G];
+  // Each loop over the candidates handles U of them per thread and trip, all loads first, so
+  // that U x G independent chains are in flight; U is matched to n, because a trip works on
+  // U x STEP_THREADS candidates whether they exist or not.
+  auto stage_and_max = [&](auto uc) {
+    constexpr int U = decltype(uc)::value;
+    for (int j0 = tid; j0 < n; j0 += U * STEP_THREADS) {
+      float v[U][G];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
         for (int gg = 0; gg < G; ++gg) v[u][gg] = gg < ng ? ld_dev(Pm + (size_t)gg * a.max_pages + j) : 0.0f;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int j = j0 + u * STEP_THREADS;
         if (j < n) {
 #pragma unroll
@@ -298,6 +312,11 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
         }
       }
     }
+  };
+  if (soft || staged) {
+    if (n <= 2 * STEP_THREADS) stage_and_max(UnrollBy<2>{});
+    else if (n <= 4 * STEP_THREADS) stage_and_max(UnrollBy<4>{});
+    else stage_and_max(UnrollBy<8>{});
   }
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) {
@@ -312,31 +331,39 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_redf[w][gg]);
     mx[gg] = v;
   }
+  FKV_SEL_MARK(1);
   // fixed-point softmax numerators in place, integer denominators (a sum of integers: no order to fix)
   unsigned long long z[G];
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) z[gg] = 0;
-  for (int j0 = tid; soft && j0 < n; j0 += 4 * STEP_THREADS) {   // 4 x G independent chains per trip
-    float v[4][G];
+  auto numerators = [&](auto uc) {
+    constexpr int U = decltype(uc)::value;
+    for (int j0 = tid; j0 < n; j0 += U * STEP_THREADS) {
+      float v[U][G];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = min(j0 + u * STEP_THREADS, n - 1);
+      for (int u = 0; u < U; ++u) {
+        const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
-      for (int gg = 0; gg < G; ++gg)
-        v[u][gg] = staged ? __uint_as_float(pw[gg * n + j]) : ld_dev(Pm + (size_t)gg * a.max_pages + j);
-    }
+        for (int gg = 0; gg < G; ++gg)
+          v[u][gg] = staged ? __uint_as_float(pw[gg * n + j]) : ld_dev(Pm + (size_t)gg * a.max_pages + j);
+      }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = j0 + u * STEP_THREADS;
+      for (int u = 0; u < U; ++u) {
+        const int j = j0 + u * STEP_THREADS;
 #pragma unroll
-      for (int gg = 0; gg < G; ++gg) {
-        const uint32_t e = softmax_fixed(v[u][gg], mx[gg]);
-        if (j < n) {
-          if (staged) pw[gg * n + j] = e;
-          z[gg] += e;
+        for (int gg = 0; gg < G; ++gg) {
+          const uint32_t e = softmax_fixed(v[u][gg], mx[gg]);
+          if (j < n) {
+            if (staged) pw[gg * n + j] = e;
+            z[gg] += e;
+          }
         }
       }
     }
+  };
+  if (soft) {
+    if (n <= 2 * STEP_THREADS) numerators(UnrollBy<2>{});
+    else numerators(UnrollBy<4>{});
   }
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) {
@@ -352,12 +379,15 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     for (int w = 0; w < STEP_WAVES; ++w) v += s_redz[w][gg];
     zd[gg] = (double)v;
   }
+  FKV_SEL_MARK(2);
   // pooled score of each candidate (each thread reads back only what it wrote); the top
   // byte of its key goes straight into the first histogram
-  for (int j0 = tid; j0 < n; j0 += 4 * STEP_THREADS) {
-    uint32_t e[4][G];                                // softmax numerators, or the bits of the weights
+  auto pool_and_key = [&](auto uc) {
+    constexpr int U = decltype(uc)::value;
+  for (int j0 = tid; j0 < n; j0 += U * STEP_THREADS) {
+    uint32_t e[U][G];                                // softmax numerators, or the bits of the weights
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
       for (int gg = 0; gg < G; ++gg) {
@@ -369,7 +399,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int j = j0 + u * STEP_THREADS;
       float sc;
       if (soft) {
@@ -399,8 +429,12 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
       }
     }
   }
+  };
+  if (n <= 2 * STEP_THREADS) pool_and_key(UnrollBy<2>{});
+  else pool_and_key(UnrollBy<4>{});
   __syncthreads();
 
+  FKV_SEL_MARK(3);
   // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
   // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
   uint32_t prefix = 0, remaining = (uint32_t)kk;
@@ -432,6 +466,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
     prefix = (prefix << 8) | bin;
   }
+  FKV_SEL_MARK(4);
   const uint32_t T = prefix;                         // the kk-th largest key
   const uint32_t take_eq = remaining;                // keys equal to T to take, lowest ids first
 
@@ -466,6 +501,12 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   }
   for (int j = tid; j < n; j += STEP_THREADS)          // pooled scores, kept for inspection
     a.score[(size_t)head * a.max_pages + lo + j] = key_score(key[j]);
+#ifdef FKV_SEL_STAMPS
+  if (a.tstamp && head == 0 && tid == 0) {
+    a.tstamp[40] = sel_t0; a.tstamp[41] = sel_t1; a.tstamp[42] = sel_t2; a.tstamp[43] = sel_t3;
+    a.tstamp[44] = sel_t4; a.tstamp[45] = wall_clock64();
+  }
+#endif
 }
 
 
