@@ -90,6 +90,8 @@ struct AttnArgs {
   int* status;               // set to 1 if a wait ran out
 };
 
+template <int CH> struct MergeChunk { static constexpr int value = CH; };
+
 // position i of a head's attend list -> HBM unit, page id and number of valid tokens; -1 if empty
 struct AttendList {
   const int32_t* ids;
@@ -363,10 +365,13 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   FKV_ASTAMP(19);
   // Every thread owns two output channels of one head and folds that head's splits with an
   // online log-sum-exp.  The (m, l) pairs and the partial outputs of up to CH splits are all
-  // requested before the first one is used: one memory round trip per CH splits, no LDS.
+  // requested before the first one is used: one memory round trip per CH splits, no LDS.  CH is
+  // matched to the number of splits: a trip issues 2 x CH device-scope loads per thread whether
+  // the splits exist or not.
   const size_t pbase = (size_t)head * a.max_splits;
   const int nt = NW * 64, items = G * D / 2;
-  constexpr int CH = 32;
+  auto merge = [&](auto chc) {
+  constexpr int CH = decltype(chc)::value;
   for (int it = threadIdx.x; it < items; it += nt) {
     const int gg = it / (D / 2), c2 = it % (D / 2);
     const float* src_o = a.part_o + (pbase * G + gg) * D + c2 * 2;
@@ -398,6 +403,13 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
     const float inv = 1.0f / den;
     *reinterpret_cast<float2*>(a.out + (size_t)(b * n_q + m * G + gg) * D + c2 * 2) = make_float2(o0 * inv, o1 * inv);
   }
+  };
+  if (a.n_splits <= 4) merge(MergeChunk<4>{});
+  else if (a.n_splits <= 8) merge(MergeChunk<8>{});
+  else if (a.n_splits <= 12) merge(MergeChunk<12>{});
+  else if (a.n_splits <= 16) merge(MergeChunk<16>{});
+  else if (a.n_splits <= 24) merge(MergeChunk<24>{});
+  else merge(MergeChunk<32>{});
   FKV_ASTAMP(21);
 #undef FKV_ASTAMP
 }

@@ -437,9 +437,15 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   FKV_SEL_MARK(3);
   // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
   // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
+  // It ends early once every key of the chosen bin is wanted: then "all keys from that bin
+  // upwards" is the answer and the lower bytes need not be resolved (every wave sees the same
+  // histogram, so the whole block takes the exit together).
   uint32_t prefix = 0, remaining = (uint32_t)kk;
+  uint32_t T = 0, take_eq = 0;                       // take keys > T, and the first take_eq keys == T
+  bool resolved = false;
 #pragma unroll
   for (int pass = 3; pass >= 0; --pass) {
+    if (resolved) continue;
     const int shift = pass * 8;
     if (pass != 3) {
       for (int j = tid; j < n; j += STEP_THREADS) {
@@ -462,13 +468,22 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     }
     const unsigned long long pick = __ballot(mine);
     const int src = __builtin_ctzll(pick);
+    const uint32_t cf = found == 0 ? c[0] : found == 1 ? c[1] : found == 2 ? c[2] : c[3];
     remaining = (uint32_t)__builtin_amdgcn_readlane((int)need, src);          // how many to take inside the bin
+    const uint32_t in_bin = (uint32_t)__builtin_amdgcn_readlane((int)cf, src); // how many it holds
     const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
     prefix = (prefix << 8) | bin;
+    if (pass == 0) {
+      T = prefix;                                    // the kk-th largest key itself;
+      take_eq = remaining;                           // of the keys equal to it, the lowest ids
+      resolved = true;
+    } else if (remaining == in_bin && (prefix << shift) != 0) {
+      T = (prefix << shift) - 1;                     // everything from the bin's lowest key upwards
+      take_eq = 0;
+      resolved = true;
+    }
   }
   FKV_SEL_MARK(4);
-  const uint32_t T = prefix;                         // the kk-th largest key
-  const uint32_t take_eq = remaining;                // keys equal to T to take, lowest ids first
 
   // ordered compaction: thread t owns the contiguous ids [t*per, (t+1)*per)
   const int per = (n + STEP_THREADS - 1) / STEP_THREADS;
@@ -499,8 +514,6 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     __hip_atomic_store(out + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (outu) outu[i] = -1;
   }
-  for (int j = tid; j < n; j += STEP_THREADS)          // pooled scores, kept for inspection
-    a.score[(size_t)head * a.max_pages + lo + j] = key_score(key[j]);
 #ifdef FKV_SEL_STAMPS
   if (a.tstamp && head == 0 && tid == 0) {
     a.tstamp[40] = sel_t0; a.tstamp[41] = sel_t1; a.tstamp[42] = sel_t2; a.tstamp[43] = sel_t3;
@@ -547,6 +560,10 @@ __device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t*
     __syncthreads();
     if (threadIdx.x == 0) __hip_atomic_store(a.sel_done + head, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  // the pooled scores, kept for inspection; after the announcement, which nothing here should delay
+  if (a.g.k_eff > 0)
+    for (int j = threadIdx.x; j < a.g.n_cand; j += STEP_THREADS)
+      a.score[(size_t)head * a.max_pages + a.g.cand_lo + j] = key_score(dyn_lds[j]);
 }
 
 }  // namespace fkv
