@@ -380,6 +380,31 @@ class FreeKVOracle:
                 out[h] = w @ Vs
         return out
 
+    # -- the pages a head attends, laid out token-major with all heads side by side (Sec. 4.2) --
+    def export_nhd(self, ids: np.ndarray, n_slots: int):
+        """The NHD-layout GPU pool of the paper's hybrid layouts, for the page lists `ids` [n_kv, k]:
+        pool [n_slots, 2 (K, V), p, n_kv, d] and slot_pages [n_kv, n_slots].  Slot s of head m holds the
+        s-th page of m's attend list -- sink pages, then the k chosen pages in the order of `ids` (an
+        unused entry leaves its slot empty), then the window pages, then the open page; an empty slot
+        has page -1 and zeros, and so have the tokens of the open page that do not exist yet."""
+        g = self.geom()
+        p = self.p
+        pool = np.zeros((n_slots, 2, p, self.n_kv, self.d), dtype=F32)
+        slot_pages = np.full((self.n_kv, n_slots), -1, dtype=np.int32)
+        for m in range(self.n_kv):
+            pages = list(range(g.n_sink)) + [int(j) for j in ids[m]] + list(range(g.n_full - g.n_win, g.n_full))
+            if g.r:
+                pages.append(g.n_full)
+            assert len(pages) <= n_slots
+            for s, page in enumerate(pages):
+                if page < 0:
+                    continue
+                n_tok = min(p, self.L - page * p)
+                slot_pages[m, s] = page
+                pool[s, 0, :n_tok, m, :] = self.K[page * p:page * p + n_tok, m, :]
+                pool[s, 1, :n_tok, m, :] = self.V[page * p:page * p + n_tok, m, :]
+        return pool, slot_pages
+
     # -- one decode step -------------------------------------------------------
     def step(self, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray) -> dict:
         self.append(k_new, v_new)

@@ -502,3 +502,36 @@ def test_variants_with_budget_covering_context_are_dense_attention(pooling):
     res = o.step(q, kn, vn)
     dense = O.dense_attention(q, np.concatenate([K, kn[None]]), np.concatenate([V, vn[None]]))
     np.testing.assert_allclose(res["out"], dense, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- Sec. 4.2: the NHD-layout pool
+def test_nhd_pool_holds_exactly_the_attended_tokens():
+    """Attention computed from the exported pool alone (valid tokens of non-empty slots, head m's
+    columns) equals the oracle's sparse attention; slot order follows the attend list."""
+    rng = np.random.default_rng(31)
+    o = O.FreeKVOracle(4, 2, 128, 4, 24, 4, 8, 0.8, 256)
+    K = _rand_T(rng, (150, 2, 128)); V = _rand_T(rng, (150, 2, 128))
+    o.load_prefix(K, V)
+    q = _rand_T(rng, (4, 128))
+    ids, _, _ = o.select(q)
+    ids[1, 1] = -1                                        # an unused entry in the middle of a list
+    n_slots = 24 // 4 + 1
+    pool, slot_pages = o.export_nhd(ids, n_slots)
+    g = o.geom()
+    assert g.r == 2 and pool.shape == (n_slots, 2, 4, 2, 128)
+    assert slot_pages[0].tolist() == [0] + ids[0].tolist() + [35, 36] + [37]
+    assert slot_pages[1, 2] == -1 and not pool[2, :, :, 1, :].any() and pool[2, :, :, 0, :].any()
+    assert not pool[6, :, 2:, :, :].any() and pool[6, :, :2, :, :].all()      # the open page has 2 tokens
+    ref = o.attend(q, ids)
+    for m in range(2):
+        ks, vs = [], []
+        for s in range(n_slots):
+            if slot_pages[m, s] >= 0:
+                n_tok = min(4, o.L - slot_pages[m, s] * 4)
+                ks.append(pool[s, 0, :n_tok, m, :]); vs.append(pool[s, 1, :n_tok, m, :])
+        ks = np.concatenate(ks).astype(np.float64); vs = np.concatenate(vs).astype(np.float64)
+        for gq in range(2):
+            h = m * 2 + gq
+            sc = ks @ q[h].astype(np.float64) / math.sqrt(128)
+            w = np.exp(sc - sc.max()); w /= w.sum()
+            np.testing.assert_allclose(w @ vs, ref[h], rtol=1e-12, atol=1e-14)
