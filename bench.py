@@ -201,6 +201,27 @@ def main():
     # duration plus the dispatch gap, the figure a kernel trace reports
     attn_ms, attn_n = ctx.profile_attn(q[n_steps - 1], out[0], max(1, K // 4), stream=stream)
 
+    # what the paper's literal GPU layout would add per layer-step: the attended pages converted
+    # to an NHD pool (tokens with all KV heads side by side) for a kernel that wants that layout
+    n_slots = wl.budget // p + 1
+    nhd_pool = torch.empty((wl.batch, n_slots, 2, p, wl.n_kv_heads, wl.head_dim), dtype=ctx.torch_dtype, device=dev)
+    nhd_pages = torch.empty((wl.batch, wl.n_kv_heads, n_slots), dtype=torch.int32, device=dev)
+    reps = 8
+    with torch.cuda.stream(stream):
+        for layer in range(wl.n_layers):
+            ctx.export_nhd(layer, nhd_pool, nhd_pages, stream=stream)
+        x0, x1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        x0.record(stream)
+        for _ in range(reps):
+            for layer in range(wl.n_layers):
+                ctx.export_nhd(layer, nhd_pool, nhd_pages, stream=stream)
+        x1.record(stream)
+    torch.cuda.synchronize()
+    nhd_us = x0.elapsed_time(x1) * 1e3 / (reps * wl.n_layers)
+    nhd = {"nhd_export_us_per_layer_step": nhd_us,
+           "nhd_export_GBps_read_plus_written": 2 * nhd_pool.numel() * 2 / (nhd_us * 1e-6) / 1e9}
+    del nhd_pool, nhd_pages
+
     extra = {}
     floor = {}
     if one_launch:
@@ -272,7 +293,7 @@ def main():
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
                    "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9,
-                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}), **extra, **prefill},
+                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}), **extra, **prefill, **nhd},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,

@@ -172,6 +172,20 @@ int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stre
 int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev,
                            int32_t use, void* stream);
 
+/* The hybrid layouts taken literally (Sec. 4.2, "Hybrid layouts" / "Streamed recall"): convert the pages
+ * that sparse attention would read with selector `use` (FKV_USE_*) into an NHD-layout pool for a
+ * kernel that wants tokens with all KV heads side by side.
+ *   nhd_pool_dev   [batch, n_slots, 2 (K, V), page_size, n_kv, d] of the storage type, device,
+ *                  16-byte aligned, written completely;
+ *   slot_pages_dev [batch, n_kv, n_slots] i32, device: the page held by each slot of each head.
+ * Slot s of head m is position s of m's attend list: sink pages, the k selected pages in the order
+ * of the page ids (an unused id leaves the slot empty), window pages, the open page.  Empty slots
+ * have page -1 and zeros; so have the tokens of the open page beyond the context.
+ * n_slots must be budget_tokens / page_size + 1.  Placement HOST: ordered behind the recall of the
+ * pages it reads, so it may run on the copy stream right behind fkv_recall_pages.  Asynchronous. */
+int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev, int32_t* slot_pages_dev,
+                   int32_t n_slots, void* stream);
+
 /* End of step: PENDING becomes ACTIVE, the staged query becomes q_prev (host-side flip). */
 int fkv_commit(fkv_ctx* ctx, int32_t layer);
 

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches",
+    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
 )
 
 
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         "fkv_sparse_decode_attn": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_commit": (C.c_int, [vp, i32]),
         "fkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
+        "fkv_export_nhd": (C.c_int, [vp, i32, i32, vp, vp, i32, vp]),
         "fkv_profile_enable": (C.c_int, [vp, i32]),
         "fkv_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "fkv_profile_attn": (C.c_int, [vp, vp, sz, vp, i32, vp, C.POINTER(C.c_double), C.POINTER(i32)]),
@@ -186,6 +187,11 @@ class FreeKV:
 
     def sparse_decode_attn(self, layer, q, out, use=FKV_USE_ACTIVE, stream=None):
         self._check(self.L.fkv_sparse_decode_attn(self._h, layer, _ptr(q), _ptr(out), use, _stream(stream)), "fkv_sparse_decode_attn")
+
+    def export_nhd(self, layer, nhd_pool, slot_pages, use=FKV_USE_ACTIVE, stream=None):
+        """nhd_pool [batch, n_slots, 2, page, n_kv, d] storage type, slot_pages [batch, n_kv, n_slots] int32."""
+        self._check(self.L.fkv_export_nhd(self._h, layer, use, _ptr(nhd_pool), _ptr(slot_pages),
+                                          slot_pages.shape[-1], _stream(stream)), "fkv_export_nhd")
 
     def commit(self, layer):
         self._check(self.L.fkv_commit(self._h, layer), "fkv_commit")

@@ -494,6 +494,28 @@ int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float
   return after_launch(ctx, "attention kernels");
 }
 
+int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev, int32_t* slot_pages_dev,
+                   int32_t n_slots, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!nhd_pool_dev || !slot_pages_dev) return ctx->fail(FKV_EINVAL, "null output");
+  if (use < 0 || use > 2) return ctx->fail(FKV_EINVAL, "bad use selector");
+  const fkv_config& c = ctx->cfg;
+  if (n_slots != c.budget_tokens / c.page_size + 1) return ctx->fail(FKV_EINVAL, "n_slots must be budget/page + 1");
+  if ((reinterpret_cast<uintptr_t>(nhd_pool_dev) & 15) != 0) return ctx->fail(FKV_EINVAL, "pool not 16-byte aligned");
+  LayerState& ls = ctx->layers[layer];
+  if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
+  if (use == FKV_USE_ACTIVE && ctx->lay.k > 0 && !ls.have_active) return ctx->fail(FKV_ESTATE, "no active selection yet");
+  if (use != FKV_USE_ACTIVE && !ls.have_pending) return ctx->fail(FKV_ESTATE, "export of the pending selection before page_select");
+  if (use == FKV_USE_BY_FLAG && !ls.have_flags) return ctx->fail(FKV_ESTATE, "export by flag before corr_check");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rcw = wait_recall(ctx, ls, st);
+  if (rcw) return rcw;
+  launch_export_nhd(ctx->dims, ctx->pool_desc(layer), ctx->ids(layer, ls.parity ^ 1), ctx->ids(layer, ls.parity),
+                    ctx->slots(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity), ctx->flags(layer), use,
+                    static_cast<uint16_t*>(nhd_pool_dev), slot_pages_dev, n_slots, make_geom(c, ls.L), st);
+  return after_launch(ctx, "NHD export kernel");
+}
+
 int fkv_commit(fkv_ctx* ctx, int32_t layer) {
   FKV_CHECK_LAYER(ctx, layer);
   LayerState& ls = ctx->layers[layer];

@@ -56,4 +56,64 @@ int launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int3
   return a.n_splits;
 }
 
+// ---------------------------------------------------------------------------------
+// The pages a head attends, converted to the NHD layout of the paper's hybrid layouts
+// (Sec. 4.2): out [batch][n_slots][2 (K, V)][page][n_kv][d], slot s of head m = position s of
+// m's attend list; slot_pages [batch][n_kv][n_slots].  One block per (slot, head): the 16 KiB
+// unit comes in with linear 16-byte loads, is turned in LDS, and goes out as 256-byte token rows.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void export_nhd_kernel(AttnArgs a, uint16_t* __restrict__ out,
+                                                         int32_t* __restrict__ slot_pages, int n_slots) {
+  __shared__ __attribute__((aligned(16))) uint16_t unit_lds[UNIT_ELEMS];
+  const int slot = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
+  const int head = b * a.n_kv + m, k = a.k;
+  const Geom& g = a.g;
+  const bool pending = a.use == 1 || (a.use == 2 && a.flags[head] != 0);
+  AttendList al;
+  al.ids = (pending ? a.new_ids : a.act_ids) + (size_t)head * k;
+  al.slots = a.pd.placement == 0 ? nullptr : (pending ? a.new_slots : a.act_slots) + (size_t)head * k;
+  al.n_sink = g.n_sink; al.k = k; al.n_win = g.n_win; al.n_full = g.n_full; al.r = g.r;
+  al.coherent_ids = false;
+  const int n_att = g.n_sink + k + g.n_win + (g.r > 0 ? 1 : 0);
+  int n_valid = 0, page = -1, unit = -1;
+  if (slot < n_att) unit = attend_unit(al, a.pd, slot, n_valid, page);
+  if (unit < 0) { page = -1; n_valid = 0; }
+  if (threadIdx.x == 0) slot_pages[(size_t)head * n_slots + slot] = page;
+  if (unit >= 0) {
+    const uint4* src = reinterpret_cast<const uint4*>(a.pd.pool + ((size_t)head * a.pd.units_per_head + unit) * UNIT_ELEMS);
+    uint4* dst = reinterpret_cast<uint4*>(unit_lds);
+#pragma unroll
+    for (int i = 0; i < UNIT_ELEMS / 8 / 256; ++i) dst[threadIdx.x + i * 256] = src[threadIdx.x + i * 256];
+  }
+  __syncthreads();
+  // 2 x 32 token rows of 16 chunks of 8 channels
+  for (int i = threadIdx.x; i < 2 * PG * (D / 8); i += 256) {
+    const int c8 = i % (D / 8), t = (i / (D / 8)) % PG, kv = i / (D / 8) / PG;
+    uint4 w = make_uint4(0, 0, 0, 0);
+    if (t < n_valid) {
+      if (kv == 0) {
+        w = *reinterpret_cast<const uint4*>(unit_lds + k_elem_off(t, c8 * 8));    // 8 channels lie together
+      } else {
+        uint16_t e[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) e[c] = unit_lds[v_elem_off(t, c8 * 8 + c)];
+        w.x = e[0] | ((uint32_t)e[1] << 16); w.y = e[2] | ((uint32_t)e[3] << 16);
+        w.z = e[4] | ((uint32_t)e[5] << 16); w.w = e[6] | ((uint32_t)e[7] << 16);
+      }
+    }
+    uint16_t* row = out + ((((size_t)(b * n_slots + slot) * 2 + kv) * PG + t) * a.n_kv + m) * D;
+    *reinterpret_cast<uint4*>(row + c8 * 8) = w;
+  }
+}
+
+void launch_export_nhd(const Dims& d, const PoolDesc& pd, const int32_t* act_ids, const int32_t* new_ids,
+                       const int32_t* act_slots, const int32_t* new_slots, const uint8_t* flags, int use,
+                       uint16_t* out, int32_t* slot_pages, int n_slots, Geom g, hipStream_t st) {
+  AttnArgs a{};
+  a.pd = pd; a.act_ids = act_ids; a.new_ids = new_ids; a.act_slots = act_slots; a.new_slots = new_slots;
+  a.flags = flags; a.use = use; a.g = g; a.n_q = d.n_q; a.n_kv = d.n_kv; a.G = d.G; a.k = d.k;
+  dim3 grid(n_slots, d.n_kv, d.batch);
+  export_nhd_kernel<<<grid, 256, 0, st>>>(a, out, slot_pages, n_slots);
+}
+
 }  // namespace fkv

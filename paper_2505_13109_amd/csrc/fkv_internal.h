@@ -90,5 +90,8 @@ int  launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int
                  int* counters, float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end,
                  long long* tstamp);
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st);
+void launch_export_nhd(const Dims& d, const PoolDesc& pd, const int32_t* act_ids, const int32_t* new_ids,
+                       const int32_t* act_slots, const int32_t* new_slots, const uint8_t* flags, int use,
+                       uint16_t* out, int32_t* slot_pages, int n_slots, Geom g, hipStream_t st);
 
 }  // namespace fkv

@@ -157,6 +157,21 @@ class Pair:
                     self.stats["picked"] += int((ref["new_ids"][m] >= 0).sum())
         return res
 
+    def check_nhd_export(self, li):
+        """The NHD-layout pool of the ACTIVE selection equals the oracle's, byte for byte."""
+        wl = self.wl
+        n_slots = wl.budget // wl.page_size + 1
+        pool = torch.full((wl.batch, n_slots, 2, wl.page_size, wl.n_kv_heads, wl.head_dim), 7.0,
+                          dtype=self.g.torch_dtype, device="cuda")
+        pages = torch.full((wl.batch, wl.n_kv_heads, n_slots), -7, dtype=torch.int32, device="cuda")
+        self.g.export_nhd(li, pool, pages)
+        got = W.decode(pool.view(torch.int16).cpu().numpy().view(np.uint16), wl.dtype)
+        for r in range(wl.batch):
+            o = self.oracles[(li, r)]
+            ref_pool, ref_pages = o.export_nhd(o.active, n_slots)
+            assert np.array_equal(pages.cpu().numpy()[r], ref_pages), f"slot pages differ: layer index {li} request {r}"
+            assert np.array_equal(got[r], ref_pool), f"NHD pool differs: layer index {li} request {r}: {_diff(got[r], ref_pool)}"
+
     def check_cached_pages(self, li, r, m, where):
         """Bytes of the picked pages where the HIP side keeps them == the bytes appended (oracle's K, V)."""
         wl = self.wl

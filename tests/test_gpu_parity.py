@@ -346,3 +346,23 @@ def test_negative_page_weights_and_long_context_selection(pooling):
             assert (score > 0).any() and ((score > 0).sum(axis=1) < g.k).all()    # negative scores get picked
         assert np.array_equal(ids.cpu().numpy()[0], ref_ids), (pooling, trial)
     g.close()
+
+
+def test_nhd_export_of_the_attended_pages():
+    """The hybrid layouts taken literally: the attended pages converted to an NHD pool, in HBM placement
+    (growing context: empty slots, partial open page, fp16, G = 7) and from the recalled page cache of the
+    host-pool placement (bf16, 2 requests)."""
+    wl = W.Workload("nhd", 1, 1, 14, 2, "fp16", 5, 256, 32, 64, 0.7, 300, 0.7, 0.714, 41, shift_every=100)
+    pr = _pair(wl, [0])
+    for t in range(wl.steps):
+        pr.step(0, t, deep=False)
+        if t % 13 == 0 or t == wl.steps - 1:
+            pr.check_nhd_export(0)
+    pr.close()
+    wl = W.get_workload("c3").scaled(batch=2, ctx=8192 - 3, steps=40)
+    pr = _pair(wl, [9], steps=40)
+    for t in range(40):
+        pr.step(0, t, deep=False)
+        if t % 8 == 7:
+            pr.check_nhd_export(0)
+    pr.close()
