@@ -40,6 +40,8 @@ static bool raise_lds(size_t lds) {
 // a second launch of one block per head selects.
 constexpr size_t kLdsPerUnit = 150 * 1024;   // of the 160 KiB of a compute unit
 constexpr int kComputeUnits = 256;
+// tuning knob for experiments: passes a scoring block makes (default: chosen from the shape)
+static int g_min_passes = [] { const char* e = getenv("FKV_LAYER_PASSES"); return e ? atoi(e) : 0; }();
 // may every block of a `grid`-block launch carry `lds` bytes without starving the scoring blocks?
 static bool lds_fits_launch(size_t lds, int grid) {
   int per_unit = (grid + kComputeUnits - 1) / kComputeUnits;   // blocks a unit should hold at once
@@ -122,7 +124,14 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
   StepArgs a;
   int grid;
   size_t lds_staged, lds_keys;
-  fill_step_args(d, roles, io, g, 1, a, grid, lds_staged, lds_keys);
+  // A scoring block lives for one memory round trip whatever it loads, so big scans get fewer
+  // blocks with more pages in flight each, as long as a few blocks per compute unit remain.
+  int passes = g_min_passes > 0 ? g_min_passes : 1;
+  if (g_min_passes <= 0 && (roles & ROLE_SELECT))
+    while (passes < SCORE_PASSES &&
+           (long)d.batch * d.n_kv * ((g.n_cand + PAGES_PER_PASS * passes * 2 - 1) / (PAGES_PER_PASS * passes * 2)) >= 4 * kComputeUnits)
+      passes *= 2;
+  fill_step_args(d, roles, io, g, passes, a, grid, lds_staged, lds_keys);
   if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
   else              launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
 }
@@ -153,8 +162,6 @@ __global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
 }
 
 static bool g_no_layer_kernel = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '1'; }();
-// tuning knob for experiments: fewest passes a scoring block makes (default: chosen from the shape)
-static int g_min_passes = [] { const char* e = getenv("FKV_LAYER_PASSES"); return e ? atoi(e) : 0; }();
 
 template <int DT, int G>
 static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
