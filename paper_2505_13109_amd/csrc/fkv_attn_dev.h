@@ -329,6 +329,7 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
     float* sm_o = lds + NW * 32;          // [NW][G][D]
     if (rb == 0) sm_m[wave * 16 + gq] = m_run;
     __syncthreads();
+    if (split == 0) FKV_ASTAMP(22);
     float M = sm_m[gq];
 #pragma unroll
     for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w * 16 + gq]);
@@ -341,6 +342,7 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
       if (rb == 0) sm_l[wave * 16 + gq] = l_run * wgt;
     }
     __syncthreads();
+    if (split == 0) FKV_ASTAMP(23);
     for (int i = threadIdx.x; i < G * D / 2; i += NW * 64) {
       const int gg = i / (D / 2), c = (i % (D / 2)) * 2;
       float s0 = 0.0f, s1 = 0.0f;
