@@ -104,6 +104,7 @@ static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, i
     lds_keys = n * sizeof(uint32_t);
     lds_staged = n * (1 + d.G) * sizeof(uint32_t);
     if (lds_staged + 8192 > (size_t)d.max_lds) lds_staged = lds_keys;   // cannot fit: do not even ask
+    if (n <= (size_t)regs_candidates(d.G)) lds_staged = lds_keys;       // few enough to stay in registers
   }
 }
 

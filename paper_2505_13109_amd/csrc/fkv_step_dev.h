@@ -241,11 +241,40 @@ __device__ __forceinline__ float key_score(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
+// pooled score of one candidate from the G per-head values e[] (softmax numerators, or the bits of
+// the weights themselves), mode = FKV_POOL_*
+template <int G>
+__device__ __forceinline__ float pooled_score(const uint32_t* e, const double* zd, int mode) {
+  if (mode <= 1) {
+    // mean (the method) or maximum over the group of the softmax values, in fp64
+    double acc = (double)e[0] / zd[0];
+#pragma unroll
+    for (int gg = 1; gg < G; ++gg) {
+      const double sg = (double)e[gg] / zd[gg];
+      if (mode == 0) acc = acc + sg;
+      else acc = sg > acc ? sg : acc;
+    }
+    return mode == 0 ? (float)(acc / (double)G) : (float)acc;
+  }
+  // mean or maximum of the weights themselves in fp32, head order; or the pooled query's weight
+  float acc = __uint_as_float(e[0]);
+#pragma unroll
+  for (int gg = 1; gg < G; ++gg) {
+    if (mode == 2) acc = acc + __uint_as_float(e[gg]);
+    else if (mode == 3) acc = fmaxf(acc, __uint_as_float(e[gg]));
+  }
+  return mode == 2 ? (float)((double)acc / (double)G) : acc;
+}
+
+// most candidates of a KV head the selection keeps in registers (G values each): 4 per thread for
+// groups up to 4, 2 per thread above
+__host__ __device__ constexpr int regs_candidates(int G) { return (G <= 4 ? 4 : 2) * STEP_THREADS; }
+
 template <int U> struct UnrollBy { static constexpr int value = U; };
 
 // phase marks of the selection, kept in registers until its end (investigation builds only)
 #ifdef FKV_SEL_STAMPS
-#define FKV_SEL_MARK(i) const long long sel_t##i = wall_clock64()
+#define FKV_SEL_MARK(i) sel_t##i = wall_clock64()
 #else
 #define FKV_SEL_MARK(i)
 #endif
@@ -271,6 +300,9 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     }
     return;
   }
+#ifdef FKV_SEL_STAMPS
+  long long sel_t0 = 0, sel_t1 = 0, sel_t2 = 0, sel_t3 = 0, sel_t4 = 0;
+#endif
   FKV_SEL_MARK(0);
   const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
   uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
@@ -282,6 +314,89 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   for (int p = 0; p < 4; ++p)
     if (tid < 256) hist[p][tid] = 0;
 
+  // A few candidates per thread stay in registers from the load to the key: no staging in LDS.
+  const bool in_regs = n <= regs_candidates(G);
+  auto front_in_regs = [&](auto uc) {
+    constexpr int U = decltype(uc)::value;
+    uint32_t e[U][G];                                  // bits of the weights, then softmax numerators
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = min(tid + u * STEP_THREADS, n - 1);
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg)
+        e[u][gg] = gg < ng ? __float_as_uint(ld_dev(Pm + (size_t)gg * a.max_pages + j)) : 0u;
+    }
+    double zd[G];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) zd[gg] = 1.0;
+    if (soft) {
+      float mx[G];
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) mx[gg] = -__builtin_inff();
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (tid + u * STEP_THREADS < n) {
+#pragma unroll
+          for (int gg = 0; gg < G; ++gg) mx[gg] = fmaxf(mx[gg], __uint_as_float(e[u][gg]));
+        }
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        const float w = wave_max_f32(mx[gg]);
+        if (lane == 0) s_redf[wave][gg] = w;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        float v = s_redf[0][gg];
+#pragma unroll
+        for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_redf[w][gg]);
+        mx[gg] = v;
+      }
+      FKV_SEL_MARK(1);
+      unsigned long long z[G];
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) z[gg] = 0;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) {
+          e[u][gg] = softmax_fixed(__uint_as_float(e[u][gg]), mx[gg]);
+          if (tid + u * STEP_THREADS < n) z[gg] += e[u][gg];
+        }
+      }
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        const unsigned long long w = wave_sum_u48(z[gg]);
+        if (lane == 0) s_redz[wave][gg] = w;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int gg = 0; gg < G; ++gg) {
+        unsigned long long v = 0;
+#pragma unroll
+        for (int w = 0; w < STEP_WAVES; ++w) v += s_redz[w][gg];
+        zd[gg] = (double)v;
+      }
+    } else {
+      FKV_SEL_MARK(1);
+    }
+    FKV_SEL_MARK(2);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = tid + u * STEP_THREADS;
+      const uint32_t kj = score_key(pooled_score<G>(e[u], zd, mode));
+      if (j < n) {
+        key[j] = kj;
+        atomicAdd(&hist[3][kj >> 24], 1u);
+      }
+    }
+  };
+  if (in_regs) {
+    if (!soft) __syncthreads();                        // the histograms are clear (else: barriers below)
+    if (n <= STEP_THREADS) front_in_regs(UnrollBy<1>{});
+    else if (n <= 2 * STEP_THREADS) front_in_regs(UnrollBy<2>{});
+    else if constexpr (regs_candidates(G) > 2 * STEP_THREADS) front_in_regs(UnrollBy<4>{});
+  } else {
   // stage the weights of this head's G query heads in LDS (one device-scope read each, 8 x G
   // of them in flight per thread) and take the per-head maximum over the candidates
   float mx[G];
@@ -401,27 +516,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = j0 + u * STEP_THREADS;
-      float sc;
-      if (soft) {
-        // mean (the method) or maximum over the group of the softmax values, in fp64
-        double acc = (double)e[u][0] / zd[0];
-#pragma unroll
-        for (int gg = 1; gg < G; ++gg) {
-          const double sg = (double)e[u][gg] / zd[gg];
-          if (mode == 0) acc = acc + sg;
-          else acc = sg > acc ? sg : acc;
-        }
-        sc = mode == 0 ? (float)(acc / (double)G) : (float)acc;
-      } else {
-        // mean or maximum of the weights themselves in fp32, head order; or the pooled query's weight
-        float acc = __uint_as_float(e[u][0]);
-#pragma unroll
-        for (int gg = 1; gg < G; ++gg) {
-          if (mode == 2) acc = acc + __uint_as_float(e[u][gg]);
-          else if (mode == 3) acc = fmaxf(acc, __uint_as_float(e[u][gg]));
-        }
-        sc = mode == 2 ? (float)((double)acc / (double)G) : acc;
-      }
+      const float sc = pooled_score<G>(e[u], zd, mode);
       const uint32_t kj = score_key(sc);
       if (j < n) {
         key[j] = kj;
@@ -432,6 +527,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   };
   if (n <= 2 * STEP_THREADS) pool_and_key(UnrollBy<2>{});
   else pool_and_key(UnrollBy<4>{});
+  }
   __syncthreads();
 
   FKV_SEL_MARK(3);
