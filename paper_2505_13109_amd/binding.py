@@ -46,7 +46,8 @@ class FkvConfig(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libfreekv.so")
+    """The in-tree library; FKV_LIB names another build of it (experiments)."""
+    return os.environ.get("FKV_LIB") or os.path.join(_HERE, "libfreekv.so")
 
 
 _lib = None

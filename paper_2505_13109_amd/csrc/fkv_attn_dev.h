@@ -130,6 +130,9 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   const int head = b * n_kv + m;
 #define FKV_ASTAMP(i) do { if (a.tstamp && head == 0 && threadIdx.x == 0) a.tstamp[i] = wall_clock64(); } while (0)
   if (split == 0) FKV_ASTAMP(16);
+#ifdef FKV_SEL_STAMPS
+  if (split == 0 && a.tstamp && threadIdx.x == 0) a.tstamp[48 + (head & 7)] = wall_clock64();
+#endif
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int gq = lane & 15, rb = lane >> 4;
   __shared__ double s_cos[MAX_G];
@@ -413,6 +416,9 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   else if (a.n_splits <= 24) merge(MergeChunk<24>{});
   else merge(MergeChunk<32>{});
   FKV_ASTAMP(21);
+#ifdef FKV_SEL_STAMPS
+  if (a.tstamp && threadIdx.x == 0) a.tstamp[32 + (head & 7)] = wall_clock64();
+#endif
 #undef FKV_ASTAMP
 }
 

@@ -16,7 +16,7 @@ namespace fkv {
 template <int DT, int G>
 __global__ __launch_bounds__(STEP_THREADS) void step_kernel(StepArgs a) {
   extern __shared__ uint32_t dyn_lds[];              // selection: n_cand keys, then G x n_cand weights
-  step_roles<DT, G>(a, blockIdx.x, dyn_lds);
+  step_roles<DT, G, false>(a, blockIdx.x, dyn_lds);
 }
 
 // Dynamic LDS above the default 64 KiB per block has to be granted per kernel function.
@@ -80,8 +80,8 @@ static void launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_s
   }
 }
 
-static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, int passes, StepArgs& a, int& grid,
-                           size_t& lds_staged, size_t& lds_keys) {
+static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, int passes, bool roomy, StepArgs& a,
+                           int& grid, size_t& lds_staged, size_t& lds_keys) {
   a = StepArgs{};
   a.roles = roles;
   a.batch = d.batch; a.n_q = d.n_q; a.n_kv = d.n_kv; a.k = d.k; a.max_pages = d.max_pages;
@@ -104,7 +104,7 @@ static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, i
     lds_keys = n * sizeof(uint32_t);
     lds_staged = n * (1 + d.G) * sizeof(uint32_t);
     if (lds_staged + 8192 > (size_t)d.max_lds) lds_staged = lds_keys;   // cannot fit: do not even ask
-    if (n <= (size_t)regs_candidates(d.G)) lds_staged = lds_keys;       // few enough to stay in registers
+    if (n <= (size_t)regs_candidates(d.G, roomy)) lds_staged = lds_keys;   // few enough to stay in registers
   }
 }
 
@@ -132,7 +132,7 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
     while (passes < SCORE_PASSES &&
            (long)d.batch * d.n_kv * ((g.n_cand + PAGES_PER_PASS * passes * 2 - 1) / (PAGES_PER_PASS * passes * 2)) >= 4 * kComputeUnits)
       passes *= 2;
-  fill_step_args(d, roles, io, g, passes, a, grid, lds_staged, lds_keys);
+  fill_step_args(d, roles, io, g, passes, false, a, grid, lds_staged, lds_keys);
   if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
   else              launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
 }
@@ -154,7 +154,7 @@ template <int DT, int G>
 __global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
   extern __shared__ uint32_t dyn_lds[];
   if ((int)blockIdx.x < a.attn_block0) {
-    step_roles<DT, G>(a.s, blockIdx.x, dyn_lds);
+    step_roles<DT, G, true>(a.s, blockIdx.x, dyn_lds);
     return;
   }
   const int ab = blockIdx.x - a.attn_block0, heads = a.s.batch * a.s.n_kv;
@@ -188,7 +188,7 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
   // the launch with scoring blocks that make `passes` passes; does every block's LDS fit?
   auto plan = [&](int passes) -> bool {
     size_t lds_staged, lds_keys;
-    fill_step_args(d, roles, io, g, passes, a.s, grid, lds_staged, lds_keys);
+    fill_step_args(d, roles, io, g, passes, true, a.s, grid, lds_staged, lds_keys);
     a.s.staged = lds_staged > lds_keys ? 1 : 0;
     a.s.fuse_select = 1;
     a.s.select_only = 0;
@@ -211,16 +211,17 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     lds = lds_staged > lds_attn ? lds_staged : lds_attn;
     return lds_fits_launch(lds, grid);
   };
-  // The kernel's registers allow one block per compute unit at a time.  Prefer the fewest passes
-  // per scoring block (most blocks) for which the whole launch is resident at once, so that no
-  // attention block queues behind the scoring blocks; if no choice gets there, the fewest passes
-  // whose LDS fits (fatter scoring blocks are also what lets big selections fit at all).
-  int chosen = 0;
+  // The kernel's registers allow one block per compute unit at a time, so a launch runs in
+  // ceil(blocks / units) rounds, and blocks of a later round (attention comes last) queue behind
+  // the scoring blocks.  Take the passes per scoring block that give the fewest rounds -- one, the
+  // whole launch resident at once, where the shape allows -- and among those the fewest passes
+  // (most blocks); fatter scoring blocks are also what lets a big selection's LDS fit at all.
+  int chosen = 0, best_rounds = 0;
   for (int passes = g_min_passes > 0 ? g_min_passes : 1; passes <= SCORE_PASSES; passes *= 2) {
     if (!plan(passes)) continue;
-    if (!chosen) chosen = passes;
+    const int rounds = (grid + kComputeUnits - 1) / kComputeUnits;
+    if (!chosen || rounds < best_rounds) { chosen = passes; best_rounds = rounds; }
     if (g_min_passes > 0) break;
-    if (grid <= kComputeUnits) { chosen = passes; break; }
   }
   const bool fits = chosen != 0 && plan(chosen);
   if (!fits) return false;                                 // big selections keep their own launches

@@ -266,9 +266,10 @@ __device__ __forceinline__ float pooled_score(const uint32_t* e, const double* z
   return mode == 2 ? (float)((double)acc / (double)G) : acc;
 }
 
-// most candidates of a KV head the selection keeps in registers (G values each): 4 per thread for
-// groups up to 4, 2 per thread above
-__host__ __device__ constexpr int regs_candidates(int G) { return (G <= 4 ? 4 : 2) * STEP_THREADS; }
+// Most candidates of a KV head the selection keeps in registers (G values each).  The layer kernel
+// has the registers for 4 per thread anyway (its attention part needs more); the step kernel alone
+// would lose occupancy of its scoring blocks above 2 per thread when G > 4.
+__host__ __device__ constexpr int regs_candidates(int G, bool roomy) { return ((roomy || G <= 4) ? 4 : 2) * STEP_THREADS; }
 
 template <int U> struct UnrollBy { static constexpr int value = U; };
 
@@ -279,7 +280,7 @@ template <int U> struct UnrollBy { static constexpr int value = U; };
 #define FKV_SEL_MARK(i)
 #endif
 
-template <int G, bool STAGED>
+template <int G, bool STAGED, bool ROOMY>
 __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32_t* key) {
   __shared__ float s_redf[STEP_WAVES][G];
   __shared__ unsigned long long s_redz[STEP_WAVES][G];
@@ -315,7 +316,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     if (tid < 256) hist[p][tid] = 0;
 
   // A few candidates per thread stay in registers from the load to the key: no staging in LDS.
-  const bool in_regs = n <= regs_candidates(G);
+  const bool in_regs = n <= regs_candidates(G, ROOMY);
   auto front_in_regs = [&](auto uc) {
     constexpr int U = decltype(uc)::value;
     uint32_t e[U][G];                                  // bits of the weights, then softmax numerators
@@ -395,7 +396,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     if (!soft) __syncthreads();                        // the histograms are clear (else: barriers below)
     if (n <= STEP_THREADS) front_in_regs(UnrollBy<1>{});
     else if (n <= 2 * STEP_THREADS) front_in_regs(UnrollBy<2>{});
-    else if constexpr (regs_candidates(G) > 2 * STEP_THREADS) front_in_regs(UnrollBy<4>{});
+    else if constexpr (regs_candidates(G, ROOMY) > 2 * STEP_THREADS) front_in_regs(UnrollBy<4>{});
   } else {
   // stage the weights of this head's G query heads in LDS (one device-scope read each, 8 x G
   // of them in flight per thread) and take the per-head maximum over the candidates
@@ -623,7 +624,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
 // role dispatch of one block: bid counts [append blocks][corr blocks][scoring blocks], each
 // set present only if its role bit is set; heads = batch * n_kv.
 // ---------------------------------------------------------------------------------
-template <int DT, int G>
+template <int DT, int G, bool ROOMY>
 __device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t* dyn_lds) {
   const int heads = a.batch * a.n_kv;
   int head;
@@ -641,15 +642,21 @@ __device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t*
     head = bid / a.blocks_per_head;
     const int chunk = bid % a.blocks_per_head;
     if (chunk == 0) FKV_STAMP(a, head, 0);
+#ifdef FKV_SEL_STAMPS
+    if (chunk == 0 && a.tstamp && threadIdx.x == 0) a.tstamp[56 + (head & 7)] = wall_clock64();
+#endif
     score_role<DT, G>(a, head, chunk);
     if (chunk == 0) FKV_STAMP(a, head, 1);
     if (!a.fuse_select) return;
     if (!last_block_done(a.counters + head, a.blocks_per_head)) return;
   }
   FKV_STAMP(a, head, 2);
-  if (a.staged) select_block<G, true>(a, head, dyn_lds);
-  else          select_block<G, false>(a, head, dyn_lds);
+  if (a.staged) select_block<G, true, ROOMY>(a, head, dyn_lds);
+  else          select_block<G, false, ROOMY>(a, head, dyn_lds);
   FKV_STAMP(a, head, 8);
+#ifdef FKV_SEL_STAMPS
+  if (a.tstamp && threadIdx.x == 0) a.tstamp[24 + (head & 7)] = wall_clock64();
+#endif
   if (a.sel_done) {
     // the ids went out with device-scope stores; once they are acknowledged, announce them
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
