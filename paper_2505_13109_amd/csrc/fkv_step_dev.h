@@ -14,7 +14,8 @@
 //   softmax: x = P - max; t = x * fl32(log2 e); n = rint(t); f = t - n;
 //            degree-6 Horner in f with separate multiply and add; ldexp(., n);
 //            0 below t < -64; E = rint(e * 2^31) as integer; Z = integer sum of E;
-//   pooling: fl32( (sum_g fp64(E_g) / fp64(Z_g), g ascending) / fp64(G) );
+//   pooling: fl32( (sum_g fp64(E_g) / fp64(Z_g), g ascending) / fp64(G) ); the quotients are the
+//            correctly rounded ones, computed from RN(1/Z_g) with fused multiply-add corrections;
 //            (alternatives, App. B.2: fl32(max_g E_g / Z_g); the fp32 sum of the weights in head
 //            order divided by G, or their maximum; the weight of the group's mean or maximum query)
 //   top-k:   radix select on the order-preserving image of the fp32 bit pattern, ties to the
@@ -241,16 +242,28 @@ __device__ __forceinline__ float key_score(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
+// The correctly rounded fp64 quotient a / b from y = RN(1 / b) (one true division per head, not per
+// candidate): q = a * y is within 1.5 ulp; one correction with the exact remainder r = a - b * q makes
+// it faithful, and for a faithful q the same correction again returns RN(a / b) (Markstein's final
+// step).  0 <= a <= b < 2^48 are integers here; no over- or underflow.
+__device__ __forceinline__ double div_rn(double a, double b, double y) {
+  double q = a * y;
+  double r = __builtin_fma(-b, q, a);
+  q = __builtin_fma(r, y, q);
+  r = __builtin_fma(-b, q, a);
+  return __builtin_fma(r, y, q);
+}
+
 // pooled score of one candidate from the G per-head values e[] (softmax numerators, or the bits of
-// the weights themselves), mode = FKV_POOL_*
+// the weights themselves), mode = FKV_POOL_*; zd = the heads' integer sums Z, zr = RN(1 / Z)
 template <int G>
-__device__ __forceinline__ float pooled_score(const uint32_t* e, const double* zd, int mode) {
+__device__ __forceinline__ float pooled_score(const uint32_t* e, const double* zd, const double* zr, int mode) {
   if (mode <= 1) {
     // mean (the method) or maximum over the group of the softmax values, in fp64
-    double acc = (double)e[0] / zd[0];
+    double acc = div_rn((double)e[0], zd[0], zr[0]);
 #pragma unroll
     for (int gg = 1; gg < G; ++gg) {
-      const double sg = (double)e[gg] / zd[gg];
+      const double sg = div_rn((double)e[gg], zd[gg], zr[gg]);
       if (mode == 0) acc = acc + sg;
       else acc = sg > acc ? sg : acc;
     }
@@ -381,11 +394,14 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     } else {
       FKV_SEL_MARK(1);
     }
+    double zr[G];
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) zr[gg] = 1.0 / zd[gg];
     FKV_SEL_MARK(2);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = tid + u * STEP_THREADS;
-      const uint32_t kj = score_key(pooled_score<G>(e[u], zd, mode));
+      const uint32_t kj = score_key(pooled_score<G>(e[u], zd, zr, mode));
       if (j < n) {
         key[j] = kj;
         atomicAdd(&hist[3][kj >> 24], 1u);
@@ -495,6 +511,9 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     for (int w = 0; w < STEP_WAVES; ++w) v += s_redz[w][gg];
     zd[gg] = (double)v;
   }
+  double zr[G];
+#pragma unroll
+  for (int gg = 0; gg < G; ++gg) zr[gg] = 1.0 / zd[gg];
   FKV_SEL_MARK(2);
   // pooled score of each candidate (each thread reads back only what it wrote); the top
   // byte of its key goes straight into the first histogram
@@ -517,7 +536,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = j0 + u * STEP_THREADS;
-      const float sc = pooled_score<G>(e[u], zd, mode);
+      const float sc = pooled_score<G>(e[u], zd, zr, mode);
       const uint32_t kj = score_key(sc);
       if (j < n) {
         key[j] = kj;
