@@ -303,6 +303,8 @@ def main():
                      "standalone_attn_kernel_us": attn_ms / max(attn_n, 1) * 1e3,
                      "event_pair_per_launch_us": pair_ms / max(pair_n, 1) * 1e3, **floor},
     }
+    for layer in range(wl.n_layers):
+        ctx.health(layer)                # no kernel gave up a bounded wait
     ctx.close()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)

@@ -44,6 +44,7 @@ extern "C" {
 #define FKV_ERANGE  -3   /* layer / page / token count out of range               */
 #define FKV_ENOMEM  -4   /* arena too small                                       */
 #define FKV_EHIP    -5   /* a HIP call failed; see fkv_last_error                 */
+#define FKV_ETIMEOUT -6  /* a kernel gave up a bounded wait for another block     */
 
 #define FKV_DTYPE_FP16 0
 #define FKV_DTYPE_BF16 1
@@ -120,6 +121,14 @@ int fkv_destroy(fkv_ctx* ctx);
 const char* fkv_last_error(const fkv_ctx* ctx);
 /* Tokens currently cached for `layer` (host-side counter), or a negative code. */
 int fkv_context_len(const fkv_ctx* ctx, int32_t layer);
+
+/* Did every kernel of `layer` so far finish its bounded waits?  In the one-launch layer-step the
+ * attention blocks of a corrected head wait for that head's selection, made by other blocks of the
+ * same launch; the wait is bounded (about 0.1 s), and a block that gives up sets a flag and goes on
+ * with whatever page ids it finds.  That is not expected to happen; this call synchronises the
+ * device, returns FKV_ETIMEOUT if it did (the layer's outputs since the previous call are then not
+ * to be trusted) and clears the flag.  Blocking. */
+int fkv_health(fkv_ctx* ctx, int32_t layer);
 
 /* Kernel launches the last fkv_decode_step of `layer` put on the compute stream: 1 when the
  * whole layer-step ran as one launch (KV in HBM, selection small enough), more otherwise. */

@@ -19,7 +19,7 @@ FKV_RECALL_GATHER, FKV_RECALL_MEMCPY = 0, 1
 DBG_SUMMARIES, DBG_WEIGHTS, DBG_SCORES, DBG_ACTIVE_IDS, DBG_PENDING_IDS, DBG_FLAGS, DBG_MISS, DBG_COSINE, DBG_TSTAMP = range(9)
 
 EXPORTED_SYMBOLS = (
-    "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len",
+    "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len", "fkv_health",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
     "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
         "fkv_destroy": (C.c_int, [vp]),
         "fkv_last_error": (C.c_char_p, [vp]),
         "fkv_context_len": (C.c_int, [vp, i32]),
+        "fkv_health": (C.c_int, [vp, i32]),
         "fkv_step_launches": (C.c_int, [vp, i32]),
         "fkv_load_prefix": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_kv_append": (C.c_int, [vp, i32, vp, vp, vp, vp]),
@@ -224,6 +225,10 @@ class FreeKV:
         self._check(self.L.fkv_profile_attn(self._h, _ptr(q_layers), stride, _ptr(out), reps, _stream(stream),
                                             C.byref(ms), C.byref(n)), "fkv_profile_attn")
         return ms.value, n.value
+
+    def health(self, layer):
+        """Raises if a kernel of this layer gave up a bounded wait (blocking)."""
+        self._check(self.L.fkv_health(self._h, layer), "fkv_health")
 
     # -- introspection ----------------------------------------------------------
     def debug_read(self, layer, what):

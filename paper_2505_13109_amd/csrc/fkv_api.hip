@@ -163,6 +163,7 @@ struct fkv_ctx {
   float* part_o() const { return reinterpret_cast<float*>(ctx_base() + lay.part_o); }
   float* part_ml() const { return reinterpret_cast<float*>(ctx_base() + lay.part_ml); }
   uint16_t* dbg_page() const { return reinterpret_cast<uint16_t*>(ctx_base() + lay.dbg_page); }
+  bool lose_selection = false;   // FKV_TEST_LOSE_SELECTION=1: corrected heads' attention waits in vain (tests the bounded wait)
   bool stamp_on = false;   // FKV_TSTAMP=1: kernels record phase timestamps of head 0 (debugging aid)
   long long* tstamp() const { return stamp_on ? reinterpret_cast<long long*>(ctx_base() + lay.tstamp) : nullptr; }
 
@@ -304,6 +305,7 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   ctx->host = cfg->placement == FKV_PLACE_HOST ? static_cast<char*>(host_arena) : nullptr;
   ctx->layers.resize(cfg->n_layers);
   { const char* e = getenv("FKV_TSTAMP"); ctx->stamp_on = e && e[0] == '1'; }
+  { const char* e = getenv("FKV_TEST_LOSE_SELECTION"); ctx->lose_selection = e && e[0] == '1'; }
   hipError_t e = hipMemset(dev_arena, 0, l.total);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
@@ -357,6 +359,18 @@ int fkv_context_len(const fkv_ctx* ctx, int32_t layer) {
   if (!ctx) return FKV_EINVAL;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return FKV_ERANGE;
   return ctx->layers[layer].L;
+}
+
+int fkv_health(fkv_ctx* ctx, int32_t layer) {
+  FKV_CHECK_LAYER(ctx, layer);
+  int flag = 0;
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  FKV_HIP(ctx, hipMemcpy(&flag, ctx->status(layer), sizeof(int), hipMemcpyDeviceToHost));
+  if (flag != 0) {
+    FKV_HIP(ctx, hipMemset(ctx->status(layer), 0, sizeof(int)));
+    return ctx->fail(FKV_ETIMEOUT, "an attention block gave up waiting for its head's selection");
+  }
+  return FKV_OK;
 }
 
 int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* V_dev, int32_t n_tokens, void* stream) {
@@ -552,6 +566,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     lio.sel_done = ctx->sel_done(layer);
     lio.epoch = ls.epoch + 1;
     lio.status = ctx->status(layer);
+    lio.attn_epoch_bias = ctx->lose_selection ? 1 : 0;
     lio.launch_grid = &ls.last_grid;
     lio.launch_lds = &ls.last_lds;
     hipEvent_t e0 = nullptr, e1 = nullptr;

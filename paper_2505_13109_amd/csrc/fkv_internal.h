@@ -68,6 +68,7 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
 struct LayerIO {
   const int32_t* act_ids; float* part_o; float* part_ml; int max_splits; int* attn_counters; float* out;
   int* sel_done; int epoch; int* status;
+  int attn_epoch_bias;                       // 0; a test of the bounded wait makes attention wait for an epoch that never comes
   int* launch_grid; size_t* launch_lds;      // out (may be null): shape of the launch that was made
 };
 // `reps` launches of a kernel that does nothing, with the given grid, 512 threads and dynamic LDS

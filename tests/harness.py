@@ -183,4 +183,6 @@ class Pair:
             assert np.array_equal(got[1], o.V[page * p:(page + 1) * p, m, :]), f"V bytes page {page}"
 
     def close(self):
+        for li in range(len(self.layers)):
+            self.g.health(li)            # no kernel gave up a bounded wait
         self.g.close()

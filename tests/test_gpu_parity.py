@@ -366,3 +366,28 @@ def test_nhd_export_of_the_attended_pages():
         if t % 8 == 7:
             pr.check_nhd_export(0)
     pr.close()
+
+
+def test_a_wait_that_runs_out_is_reported(monkeypatch):
+    """The bounded wait of a corrected head's attention blocks: with FKV_TEST_LOSE_SELECTION=1 they wait for
+    an announcement that never comes; every kernel still ends, and fkv_health reports it once."""
+    import paper_2505_13109_amd as fkv
+    from harness import to_dev
+    monkeypatch.setenv("FKV_TEST_LOSE_SELECTION", "1")
+    g = fkv.FreeKV(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, max_ctx=4096, budget=512, sink=64,
+                   window=64, tau=1.5, dtype="bf16")
+    monkeypatch.delenv("FKV_TEST_LOSE_SELECTION")
+    rng = np.random.default_rng(3)
+    kv = to_dev(W.encode(rng.standard_normal((1, 3000, 2, 128)).astype(np.float32), "bf16"), "bf16")
+    g.load_prefix(0, kv, kv)
+    q = to_dev(W.encode(rng.standard_normal((1, 8, 128)).astype(np.float32), "bf16"), "bf16")
+    kn = to_dev(W.encode(rng.standard_normal((1, 2, 128)).astype(np.float32), "bf16"), "bf16")
+    out = torch.empty((1, 8, 128), dtype=torch.float32, device="cuda")
+    g.health(0)
+    g.decode_step(0, q, kn, kn, out)
+    assert g.step_launches(0) == 1
+    with pytest.raises(fkv.FreeKVError, match="gave up waiting"):
+        g.health(0)
+    g.health(0)                                        # reported once, then clear
+    assert torch.isfinite(out).all()
+    g.close()
