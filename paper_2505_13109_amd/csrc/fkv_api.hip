@@ -92,7 +92,7 @@ const char* check_config(const fkv_config* c) {
   if (c->sink_tokens < 0 || c->window_tokens < 0 || c->budget_tokens < c->sink_tokens + c->window_tokens) return "budget must cover sink + window";
   if (c->dtype != FKV_DTYPE_FP16 && c->dtype != FKV_DTYPE_BF16) return "dtype must be fp16 or bf16";
   if (c->placement != FKV_PLACE_HBM && c->placement != FKV_PLACE_HOST) return "bad placement";
-  if ((size_t)(c->max_ctx / PG) * 4 + 4096 > 65536) return "max_ctx above 503808 tokens is not supported (top-k keys live in LDS)";
+  if ((size_t)(c->max_ctx / PG) * 4 + 4096 > 65536) return "max_ctx above 491520 tokens is not supported (top-k keys live in LDS)";
   if ((c->budget_tokens - c->sink_tokens - c->window_tokens) / PG > 1024) return "more than 1024 selectable pages are not supported";
   if (c->tau != c->tau) return "tau is NaN";
   if (c->recall_mode != FKV_RECALL_GATHER && c->recall_mode != FKV_RECALL_MEMCPY) return "bad recall_mode";

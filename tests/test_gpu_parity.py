@@ -391,3 +391,32 @@ def test_a_wait_that_runs_out_is_reported(monkeypatch):
     g.health(0)                                        # reported once, then clear
     assert torch.isfinite(out).all()
     g.close()
+
+
+def test_longest_supported_context():
+    """max_ctx at its limit (491520 tokens, 15360 pages; G = 8): one more page is refused at creation, and
+    a selection and a whole decode step over 15.3K candidate pages match the oracle."""
+    import paper_2505_13109_amd as fkv
+    from harness import to_dev, rel_err_per_head
+    cfg = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=1, budget=2048, sink=512, window=512, tau=0.8, dtype="bf16")
+    with pytest.raises(fkv.FreeKVError):
+        fkv.FreeKV(max_ctx=491520 + 32, **cfg)
+    g = fkv.FreeKV(max_ctx=491520, **cfg)
+    wl = W.Workload("max", 1, 1, 8, 1, "bf16", 491520 - 40, 2048, 512, 512, 0.8, 2, 0.9, 0.436, 51)
+    (K, Kb), (V, Vb) = W.kv_prefix(wl, 0, 0)
+    o = O.FreeKVOracle(8, 1, 128, 32, 2048, 512, 512, 0.8, 491520)
+    o.load_prefix_bulk(K, V)
+    g.load_prefix(0, to_dev(Kb[None], "bf16"), to_dev(Vb[None], "bf16"))
+    q, qb = W.query_stream(wl, 0, 0)
+    (kd, kdb), (vd, vdb) = W.kv_decode_tokens(wl, 0, 0)
+    out = torch.empty((1, 8, 128), dtype=torch.float32, device="cuda")
+    from paper_2505_13109_amd import binding as B
+    for t in range(2):
+        g.decode_step(0, to_dev(qb[t][None], "bf16"), to_dev(kdb[t][None], "bf16"), to_dev(vdb[t][None], "bf16"), out)
+        ref = o.step(q[t], kd[t], vd[t])
+        assert ref["geom"].n_cand > 15300
+        assert np.array_equal(g.debug_read(0, B.DBG_ACTIVE_IDS)[0], ref["new_ids"]), t
+        assert np.array_equal(g.debug_read(0, B.DBG_FLAGS)[0], ref["flags"]), t
+        assert rel_err_per_head(out.cpu().numpy()[0], ref["out"]).max() <= 2e-3
+    g.health(0)
+    g.close()
