@@ -107,6 +107,9 @@ def main():
                     help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
                          "a labelled stand-in for the layer's QKV/FFN weight reads that recall overlaps with in a "
                          "real model (never part of the default run)")
+    ap.add_argument("--real-layer", action="store_true",
+                    help="design-note run: a Llama-shaped layer (QKV, RoPE, o_proj, SwiGLU FFN; random weights, "
+                         "library GEMVs) around every layer-step, to see how much recall hides behind real compute")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run a plain elementwise kernel of known size (reads and writes 256 MiB) three "
                          "times: the yardstick for HBM byte counters collected over this command")
@@ -169,11 +172,42 @@ def main():
         standin = torch.ones(args.standin_mb * 1000 * 1000 // 2, dtype=torch.bfloat16, device=dev)
         sink_val = torch.zeros((1,), dtype=torch.float32, device=dev)
 
+    real = None
+    if args.real_layer:
+        # The rest of a decoder layer, for its cost and its place on the stream only: hidden = n_q * d,
+        # FFN 3.5 x hidden (Llama-3.1-8B: 4096 / 14336, 436 MB of weights per layer), random weights,
+        # distinct per layer.  The loop's own q, k, v stay the seeded synthetic streams, so that the reuse
+        # and correction statistics remain the workload's; the projections are computed and dropped.
+        hid, ffn, dt = wl.n_q_heads * wl.head_dim, int(3.5 * wl.n_q_heads * wl.head_dim), ctx.torch_dtype
+        qkv_out = (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim
+        g = torch.Generator(device=dev).manual_seed(7)
+        mk = lambda *s: (torch.randn(*s, generator=g, device=dev, dtype=torch.float32) * 0.02).to(dt)
+        real = {"wqkv": [mk(hid, qkv_out) for _ in range(wl.n_layers)], "wo": [mk(hid, hid) for _ in range(wl.n_layers)],
+                "wgu": [mk(hid, 2 * ffn) for _ in range(wl.n_layers)], "wd": [mk(ffn, hid) for _ in range(wl.n_layers)],
+                "x": mk(wl.batch, hid) * 50, "cos": mk(1, 1, wl.head_dim // 2) * 50, "sin": mk(1, 1, wl.head_dim // 2) * 50,
+                "weight_MB_per_layer": (hid * qkv_out + hid * hid + 3 * hid * ffn) * 2 / 1e6}
+
+        def rms(x):
+            return x * torch.rsqrt(x.float().pow(2).mean(-1, keepdim=True) + 1e-5).to(x.dtype)
+
+        def rope(x):
+            a, b2 = x[..., : wl.head_dim // 2], x[..., wl.head_dim // 2:]
+            return torch.cat([a * real["cos"] - b2 * real["sin"], a * real["sin"] + b2 * real["cos"]], dim=-1)
+
     def run(t0, t1):
         for t in range(t0, t1):
+            x = real["x"] if real else None
             for layer in range(wl.n_layers):
+                if real:
+                    qkv = (rms(x) @ real["wqkv"][layer]).view(wl.batch, -1, wl.head_dim)
+                    rope(qkv[:, : wl.n_q_heads + wl.n_kv_heads])
                 ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer],
                                 stream=stream, copy_stream=copy_stream)
+                if real:
+                    x = x + out[layer].to(x.dtype).view(wl.batch, -1) @ real["wo"][layer]
+                    gu = rms(x) @ real["wgu"][layer]
+                    half = gu.shape[-1] // 2
+                    x = x + (torch.nn.functional.silu(gu[:, :half]) * gu[:, half:]) @ real["wd"][layer]
                 if standin is not None:
                     torch.sum(standin, dim=(0,), keepdim=True, dtype=torch.float32, out=sink_val)
 
@@ -293,7 +327,10 @@ def main():
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
                    "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9,
-                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}), **extra, **prefill, **nhd},
+                   **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}),
+                   **({"real_layer": "QKV + RoPE + o_proj + SwiGLU FFN GEMVs with random weights around every layer-step "
+                                     "(library GEMVs; the loop's q, k, v stay the synthetic streams)",
+                       "real_layer_weight_MB": real["weight_MB_per_layer"]} if real else {}), **extra, **prefill, **nhd},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
