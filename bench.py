@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (stated in config.workload)")
     ap.add_argument("--recall-mode", type=int, default=0, help="placement 1: 0 gather kernel, 1 hipMemcpyAsync per unit")
     ap.add_argument("--placement", type=int, default=-1, help="override KV placement: 0 HBM, 1 pinned host pool")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of requests (stated in config.workload)")
     ap.add_argument("--tau", type=float, default=None, help="override the correction threshold (stated in config.workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--standin-mb", type=int, default=0,
@@ -130,6 +131,8 @@ def main():
         wl = wl.scaled(placement=args.placement)
     if args.tau is not None:
         wl = wl.scaled(tau=args.tau)
+    if args.batch > 0:
+        wl = wl.scaled(batch=args.batch)
     if args.calibration_copy:
         a = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda:0")
         for _ in range(3):

@@ -134,8 +134,8 @@ __device__ __forceinline__ void corr_role(const StepArgs& a, int head) {
 // kmin (one 16-byte load each, 1 KiB contiguous per wave and array), so a wave
 // scores 4 pages and a block 16 pages.
 // ---------------------------------------------------------------------------------
-template <int DT, int G>
-__device__ __forceinline__ void score_role(const StepArgs& a, int head, int chunk) {
+template <int DT, int G, bool QMODE>
+__device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chunk) {
   const int b = head / a.n_kv, m = head % a.n_kv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane >> 4, c8 = lane & 15;
@@ -162,8 +162,8 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
   }
   // Variants that pool the QUERY over the group (App. B.2, MeanQ / MaxQ): one pooled query per KV
   // head takes the place of head 0 of the group, and only its row of P is written.
-  const bool qmode = a.sel_pool >= 4;
-  if (qmode) {
+  constexpr int NG = QMODE ? 1 : G;                       // rows of P this launch writes per KV head
+  if (QMODE) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       float acc = f[0][c];
@@ -175,20 +175,21 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
     }
   }
   const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
+  float* const prow = a.P + (size_t)(b * a.n_q + m * G + (c8 < NG ? c8 : 0)) * a.max_pages;
 #pragma unroll
   for (int ps = 0; ps < SCORE_PASSES; ++ps) {
     if (ps >= a.passes) break;
     float kx[8], kn[8];
     unpack8<DT>(wmax[ps], kx);
     unpack8<DT>(wmin[ps], kn);
+    float mine = 0.0f;                                    // the total of query head c8, for lanes c8 < NG
 #pragma unroll
-    for (int gg = 0; gg < G; ++gg) {
-      if (qmode && gg > 0) break;
+    for (int gg = 0; gg < NG; ++gg) {
       // chunk sum, left to right.  The product q_c * (q_c >= 0 ? kmax_c : kmin_c) of two 16-bit
       // floats is exact in fp32, so the fma rounds once, exactly like "s + product"; a mean
       // query is a full fp32 number, so there the product is rounded on its own first.
       float s;
-      if (qmode) {
+      if (QMODE) {
         s = f[0][0] * (f[0][0] >= 0.0f ? kx[0] : kn[0]);
 #pragma unroll
         for (int c = 1; c < 8; ++c) {
@@ -201,15 +202,23 @@ __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chun
         for (int c = 0; c < 8; ++c) s = __builtin_fmaf(f[gg][c], f[gg][c] >= 0.0f ? kx[c] : kn[c], s);
       }
       // adjacent-pair tree over the 16 chunk sums (xor 1, 2 in quads; the mirrors pair lanes
-      // that hold equal partial sums' complements, which is the same tree)
+      // that hold equal partial sums' complements, which is the same tree); every lane ends up
+      // with the total
       s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0xB1, 0xf, 0xf, false));
       s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x4E, 0xf, 0xf, false));
       s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x141, 0xf, 0xf, false));
       s = s + __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(s), 0x140, 0xf, 0xf, false));
-      const float w = s * scale;
-      if (c8 == gg && page[ps] >= 0) st_dev(a.P + (size_t)(b * a.n_q + m * G + gg) * a.max_pages + page[ps], w);
+      mine = c8 == gg ? s : mine;
     }
+    // one store per pass: lane c8 of a page's 16 lanes writes the weight of query head c8
+    if (c8 < NG && page[ps] >= 0) st_dev(prow + page[ps], mine * scale);
   }
+}
+
+template <int DT, int G>
+__device__ __forceinline__ void score_role(const StepArgs& a, int head, int chunk) {
+  if (a.sel_pool >= 4) score_pages<DT, G, true>(a, head, chunk);
+  else                 score_pages<DT, G, false>(a, head, chunk);
 }
 
 // ---------------------------------------------------------------------------------
