@@ -22,7 +22,15 @@ int attn_pages_per_block(int n_att, int heads, int max_splits, int nw) {
   int pps = nw;
   while (pps < 16 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
   while ((n_att + pps - 1) / pps > 32 && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 128) pps *= 2;
+  // With many heads the launch is bandwidth-bound and what counts is the fixed cost of a block
+  // (its partial, the counter, the merge): measured best at about one block per compute unit,
+  // down to one block per head.
+  while (pps < n_att && (long)heads * ((n_att + pps * 2 - 1) / (pps * 2)) >= 256) pps *= 2;
   while ((n_att + pps - 1) / pps > (max_splits < MAX_MERGE_SPLITS ? max_splits : MAX_MERGE_SPLITS)) pps *= 2;
+  if (pps > 16) {                                   // long blocks: split the head evenly
+    const int n_splits = (n_att + pps - 1) / pps;
+    pps = (n_att + n_splits - 1) / n_splits;
+  }
   if (g_pps_override > 0) pps = g_pps_override;
   return pps;
 }

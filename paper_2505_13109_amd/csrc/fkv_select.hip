@@ -40,6 +40,9 @@ static bool raise_lds(size_t lds) {
 // a second launch of one block per head selects.
 constexpr size_t kLdsPerUnit = 150 * 1024;   // of the 160 KiB of a compute unit
 constexpr int kComputeUnits = 256;
+constexpr int kFuseMaxBlocks = kComputeUnits;       // launches up to this size run the selection in their last scoring blocks
+constexpr int kLayerMaxBlocks = 4 * kComputeUnits;  // shapes up to this size take the one-launch layer kernel
+static int g_fuse_mode = [] { const char* e = getenv("FKV_FUSE_SELECT"); return e ? atoi(e) : -1; }();   // experiments: 0 never, 1 always
 // tuning knob for experiments: passes a scoring block makes (default: chosen from the shape)
 static int g_min_passes = [] { const char* e = getenv("FKV_LAYER_PASSES"); return e ? atoi(e) : 0; }();
 // may every block of a `grid`-block launch carry `lds` bytes without starving the scoring blocks?
@@ -61,7 +64,10 @@ static void launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, s
     a.staged = 0;
   }
   if (select && !a.staged && lds > kDefaultLimit) (void)raise_lds<DT, G>(lds);
-  a.fuse_select = (select && lds_fits_launch(lds, grid)) ? 1 : 0;
+  // In a launch of many rounds the scoring blocks should end the moment their weights are on the
+  // way: waiting for the stores' acknowledgement and the counter (what the fused selection needs)
+  // would hold the unit's slots for several memory round trips per block.
+  a.fuse_select = (select && lds_fits_launch(lds, grid) && (g_fuse_mode < 0 ? grid <= kFuseMaxBlocks : g_fuse_mode == 1)) ? 1 : 0;
   a.select_only = 0;
   step_kernel<DT, G><<<grid, STEP_THREADS, a.fuse_select ? lds : 0, st>>>(a);
   if (select && !a.fuse_select) {
@@ -163,6 +169,7 @@ __global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
 }
 
 static bool g_no_layer_kernel = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '1'; }();
+static bool g_layer_always = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '0'; }();   // experiments
 
 template <int DT, int G>
 static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
@@ -223,7 +230,9 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     if (!chosen || rounds < best_rounds) { chosen = passes; best_rounds = rounds; }
     if (g_min_passes > 0) break;
   }
-  const bool fits = chosen != 0 && plan(chosen);
+  // Big shapes are bandwidth-bound, not latency-bound: there the separate kernels, with their
+  // smaller register footprints and blocks that never wait, stream faster than this one.
+  const bool fits = chosen != 0 && plan(chosen) && (grid <= kLayerMaxBlocks || g_layer_always);
   if (!fits) return false;                                 // big selections keep their own launches
   if (lio.launch_grid) *lio.launch_grid = grid;
   if (lio.launch_lds) *lio.launch_lds = lds;
