@@ -420,3 +420,16 @@ def test_longest_supported_context():
         assert rel_err_per_head(out.cpu().numpy()[0], ref["out"]).max() <= 2e-3
     g.health(0)
     g.close()
+
+
+def test_many_requests_take_the_bandwidth_bound_dispatch():
+    """40 requests x 8 KV heads: past the size of the one-launch layer kernel, so the step runs as separate
+    launches with the selection in a launch of its own and one attention block per head."""
+    wl = W.Workload("many", 1, 40, 32, 8, "bf16", 3000, 512, 64, 64, 0.8, 6, 0.8, 0.6, 61)
+    pr = _pair(wl, [0])
+    for t in range(wl.steps):
+        pr.step(0, t, deep=(t % 2 == 0))
+    assert pr.g.step_launches(0) > 1
+    assert 0 < pr.stats["flagged"] < pr.stats["heads"]
+    print("many", pr.stats)
+    pr.close()
