@@ -67,6 +67,47 @@ def gen_inputs(torch, wl, n_steps, device):
     return kv, q, k_new, v_new
 
 
+def saturated_rate(torch, fkv, wl, batch, layers=2, steps=16, warmup=4):
+    """The same shape with `batch` requests and few layers: enough bytes per launch for the path to be
+    bound by HBM bandwidth instead of by its chain of dependent memory round trips."""
+    ws = wl.scaled(batch=batch, n_layers=layers)
+    dev = torch.device("cuda:0")
+    p = ws.page_size
+    n_steps = steps + warmup
+    ctx = fkv.FreeKV(n_layers=layers, batch=batch, n_q_heads=ws.n_q_heads, n_kv_heads=ws.n_kv_heads,
+                     max_ctx=((ws.ctx + n_steps + 16 + p - 1) // p) * p, budget=ws.budget, sink=ws.sink,
+                     window=ws.window, tau=ws.tau, dtype=ws.dtype, placement=0)
+    kv, q, k_new, v_new = gen_inputs(torch, ws, n_steps, dev)
+    for layer in range(layers):
+        ctx.load_prefix(layer, kv((batch, ws.ctx, ws.n_kv_heads, ws.head_dim)), kv((batch, ws.ctx, ws.n_kv_heads, ws.head_dim)))
+    out = torch.empty((layers, batch, ws.n_q_heads, ws.head_dim), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def run(t0, t1):
+        for t in range(t0, t1):
+            for layer in range(layers):
+                ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer], stream=stream)
+
+    run(0, warmup)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    run(warmup, n_steps)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t_begin) / (steps * layers) * 1e6
+    attn_ms, attn_n = ctx.profile_attn(q[n_steps - 1], out[0], 4, stream=stream)
+    for layer in range(layers):
+        ctx.health(layer)
+    launches = ctx.step_launches(0)
+    ctx.close()
+    score_b, attn_b = algorithmic_bytes(ws)
+    return {"batch": batch, "layers": layers, "steps": steps, "launches_per_layer_step": launches,
+            "us_per_layer_step": us, "algorithmic_MB_per_layer_step": (score_b + attn_b) / 1e6,
+            "path_algorithmic_GBps": (score_b + attn_b) / us / 1e3,
+            "path_frac_of_hbm_peak": (score_b + attn_b) / us / 1e3 / HBM_PEAK_GBPS,
+            "attn_kernel_GBps": attn_b / (attn_ms / attn_n * 1e-3) / 1e9,
+            "attn_kernel_frac_of_hbm_peak": attn_b / (attn_ms / attn_n * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
 def cpu_baseline(wl, budget_s=12.0):
     """The oracle as it stands, one thread, on a bounded sample: one layer of the same workload."""
     import numpy as np
@@ -108,6 +149,9 @@ def main():
                     help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
                          "a labelled stand-in for the layer's QKV/FFN weight reads that recall overlaps with in a "
                          "real model (never part of the default run)")
+    ap.add_argument("--saturation-batch", type=int, default=32,
+                    help="also time the same shape with this many requests (2 layers, KV in HBM), where the path is "
+                         "bandwidth-bound; reported as config.saturated_shape; 0 = skip")
     ap.add_argument("--real-layer", action="store_true",
                     help="design-note run: a Llama-shaped layer (QKV, RoPE, o_proj, SwiGLU FFN; random weights, "
                          "library GEMVs) around every layer-step, to see how much recall hides behind real compute")
@@ -346,6 +390,10 @@ def main():
     for layer in range(wl.n_layers):
         ctx.health(layer)                # no kernel gave up a bounded wait
     ctx.close()
+    del kv, q, k_new, v_new, out
+    torch.cuda.empty_cache()
+    if args.saturation_batch > 0 and wl.name == "c2" and args.batch == 0 and not args.real_layer and not args.standin_mb:
+        res["config"]["saturated_shape"] = saturated_rate(torch, fkv, wl, args.saturation_batch)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))

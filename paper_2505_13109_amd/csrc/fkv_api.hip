@@ -27,6 +27,7 @@ struct LayerState {
   bool recall_outstanding = false;
   int epoch = 0;             // decode steps taken through the one-launch path (selection epochs)
   int last_launches = 0;     // kernel launches of the last fkv_decode_step (compute stream)
+  int step_launches = 0;     // launches the last run_step made
   int last_grid = 0;         // grid and dynamic LDS of the last one-launch layer-step
   size_t last_lds = 0;
   hipEvent_t ev_offload = nullptr;   // last page offload finished
@@ -234,7 +235,7 @@ static StepIO make_step_io(fkv_ctx* ctx, int layer, const void* q, const void* k
 static int run_step(fkv_ctx* ctx, int layer, int roles, const void* q, const void* k_new, const void* v_new,
                     uint8_t* flags_user, int32_t* ids_user, int L_after, hipStream_t st) {
   const StepIO io = make_step_io(ctx, layer, q, k_new, v_new, flags_user, ids_user);
-  launch_step(ctx->dims, roles, io, make_geom(ctx->cfg, L_after), st);
+  ctx->layers[layer].step_launches = launch_step(ctx->dims, roles, io, make_geom(ctx->cfg, L_after), st);
   return after_launch(ctx, "step kernel");
 }
 
@@ -621,7 +622,8 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     if (rc) return rc;
   }
   ls.recall_outstanding = deferred;
-  ls.last_launches = host_pool ? 5 : 2;
+  // step roles (1-3) + attention, and with the host pool the plan and the corrected heads' gather
+  ls.last_launches = ls.step_launches + 1 + (host_pool ? 2 : 0);
   return fkv_commit(ctx, layer);
 }
 

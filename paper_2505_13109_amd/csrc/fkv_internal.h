@@ -62,7 +62,7 @@ struct StepIO {
   float* P; float* score; int32_t* ids; int32_t* ids_user; int* counters;            // selection
   long long* tstamp;                                                                 // debug timestamps or null
 };
-void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st);
+int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st);   // returns the launches made
 // the whole layer-step (step roles + attention) in one launch; false if this shape or placement
 // has to take the separate launches
 struct LayerIO {

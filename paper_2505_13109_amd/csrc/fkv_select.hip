@@ -54,7 +54,7 @@ static bool lds_fits_launch(size_t lds, int grid) {
 }
 
 template <int DT, int G>
-static void launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
   constexpr size_t kDefaultLimit = 64 * 1024 - 8 * 1024;   // minus this kernel's static LDS, rounded up
   const bool select = (a.roles & ROLE_SELECT) != 0;
   size_t lds = lds_staged;
@@ -73,16 +73,18 @@ static void launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, s
   if (select && !a.fuse_select) {
     a.select_only = 1;
     step_kernel<DT, G><<<heads, STEP_THREADS, lds, st>>>(a);
+    return 2;
   }
+  return 1;
 }
 
 template <int DT>
-static void launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+static int launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
   switch (G) {
-#define FKV_CASE(GG) case GG: launch_step_g<DT, GG>(a, grid, heads, lds_staged, lds_keys, st); break;
+#define FKV_CASE(GG) case GG: return launch_step_g<DT, GG>(a, grid, heads, lds_staged, lds_keys, st);
     FKV_CASE(1) FKV_CASE(2) FKV_CASE(3) FKV_CASE(4) FKV_CASE(5) FKV_CASE(6) FKV_CASE(7) FKV_CASE(8)
 #undef FKV_CASE
-    default: break;
+    default: return 0;
   }
 }
 
@@ -121,11 +123,12 @@ static bool append_races_selection(int roles, const Geom& g) {
   return (roles & ROLE_APPEND) && (roles & ROLE_SELECT) && g.r == 0 && g.n_win == 0 && g.n_cand > 0;
 }
 
-void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st) {
+int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st) {
   if (d.k == 0) roles &= ~ROLE_SELECT;
-  if (roles == 0) return;
+  if (roles == 0) return 0;
+  int launches = 0;
   if (append_races_selection(roles, g)) {      // then the append gets a launch of its own first
-    launch_step(d, ROLE_APPEND, io, g, st);
+    launches += launch_step(d, ROLE_APPEND, io, g, st);
     roles &= ~ROLE_APPEND;
   }
   StepArgs a;
@@ -139,8 +142,9 @@ void launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t
            (long)d.batch * d.n_kv * ((g.n_cand + PAGES_PER_PASS * passes * 2 - 1) / (PAGES_PER_PASS * passes * 2)) >= 4 * kComputeUnits)
       passes *= 2;
   fill_step_args(d, roles, io, g, passes, false, a, grid, lds_staged, lds_keys);
-  if (d.dtype == 0) launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
-  else              launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
+  if (d.dtype == 0) launches += launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
+  else              launches += launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
+  return launches;
 }
 
 // ---------------------------------------------------------------------------------
