@@ -42,6 +42,7 @@ constexpr size_t kLdsPerUnit = 150 * 1024;   // of the 160 KiB of a compute unit
 constexpr int kComputeUnits = 256;
 constexpr int kFuseMaxBlocks = kComputeUnits;       // launches up to this size run the selection in their last scoring blocks
 constexpr int kLayerMaxBlocks = 4 * kComputeUnits;  // shapes up to this size take the one-launch layer kernel
+static int g_chunks_per_block = [] { const char* e = getenv("FKV_SCORE_CHUNKS"); return e ? atoi(e) : 0; }();   // experiments
 static int g_fuse_mode = [] { const char* e = getenv("FKV_FUSE_SELECT"); return e ? atoi(e) : -1; }();   // experiments: 0 never, 1 always
 // tuning knob for experiments: passes a scoring block makes (default: chosen from the shape)
 static int g_min_passes = [] { const char* e = getenv("FKV_LAYER_PASSES"); return e ? atoi(e) : 0; }();
@@ -89,7 +90,7 @@ static int launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_st
 }
 
 static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, int passes, bool roomy, StepArgs& a,
-                           int& grid, size_t& lds_staged, size_t& lds_keys) {
+                           int& grid, size_t& lds_staged, size_t& lds_keys, int chunks_per_block = 1) {
   a = StepArgs{};
   a.roles = roles;
   a.batch = d.batch; a.n_q = d.n_q; a.n_kv = d.n_kv; a.k = d.k; a.max_pages = d.max_pages;
@@ -101,7 +102,8 @@ static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, i
   a.P = io.P; a.score = io.score; a.ids = io.ids; a.ids_user = io.ids_user; a.counters = io.counters; a.tstamp = io.tstamp;
   const int heads = d.batch * d.n_kv;
   a.passes = passes;
-  a.blocks_per_head = g.n_cand > 0 ? (g.n_cand + PAGES_PER_PASS * passes - 1) / (PAGES_PER_PASS * passes) : 1;
+  const int chunks = g.n_cand > 0 ? (g.n_cand + PAGES_PER_PASS * passes - 1) / (PAGES_PER_PASS * passes) : 1;
+  a.blocks_per_head = (chunks + chunks_per_block - 1) / chunks_per_block;
   grid = 0;
   lds_staged = lds_keys = 0;
   if (roles & ROLE_APPEND) grid += heads;
@@ -141,7 +143,15 @@ int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t 
     while (passes < SCORE_PASSES &&
            (long)d.batch * d.n_kv * ((g.n_cand + PAGES_PER_PASS * passes * 2 - 1) / (PAGES_PER_PASS * passes * 2)) >= 4 * kComputeUnits)
       passes *= 2;
-  fill_step_args(d, roles, io, g, passes, false, a, grid, lds_staged, lds_keys);
+  // ... and beyond a few blocks per unit, a block takes several chunks in turn: a block's fixed cost
+  // (dispatch, the query loads, the drain of its stores) is what is left to save once the scan
+  // streams
+  int chunks_per_block = g_chunks_per_block > 0 ? g_chunks_per_block : 1;
+  if (g_chunks_per_block <= 0 && (roles & ROLE_SELECT)) {
+    const long blocks = (long)d.batch * d.n_kv * ((g.n_cand + PAGES_PER_PASS * passes - 1) / (PAGES_PER_PASS * passes));
+    while (chunks_per_block < 16 && blocks / chunks_per_block > 4 * kComputeUnits) chunks_per_block *= 2;
+  }
+  fill_step_args(d, roles, io, g, passes, false, a, grid, lds_staged, lds_keys, chunks_per_block);
   if (d.dtype == 0) launches += launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
   else              launches += launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
   return launches;

@@ -66,7 +66,7 @@ struct StepArgs {
   int32_t* ids;
   int32_t* ids_user;
   int* counters;
-  int blocks_per_head;
+  int blocks_per_head;       // scoring blocks of a KV head; block i takes chunks i, i + blocks_per_head, ...
   int passes;                // passes of PAGES_PER_PASS pages a scoring block makes (1 .. SCORE_PASSES)
   int staged;                // the G x n_cand weights fit in LDS next to the keys
   int fuse_select;           // the last scoring block of a head runs its selection (else: a second launch does)
@@ -139,21 +139,24 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
   const int b = head / a.n_kv, m = head % a.n_kv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane >> 4, c8 = lane & 15;
-  const int pages_per_block = PAGES_PER_PASS * a.passes;
-  if (chunk * pages_per_block >= a.g.n_cand) return;      // a block that only exists to run the selection
-  // all summary loads of the block's passes first, then q: everything is in flight at once
+  const int pages_per_chunk = PAGES_PER_PASS * a.passes;
+  if (chunk * pages_per_chunk >= a.g.n_cand) return;      // a block that only exists to run the selection
+  // all summary loads of a chunk's passes first, then q: everything is in flight at once
   uint4 wmax[SCORE_PASSES], wmin[SCORE_PASSES];
   int page[SCORE_PASSES];
+  auto load_chunk = [&](int ch) {
 #pragma unroll
-  for (int ps = 0; ps < SCORE_PASSES; ++ps) {
-    const int j = chunk * pages_per_block + ps * PAGES_PER_PASS + wave * 4 + grp;
-    page[ps] = (ps < a.passes && j < a.g.n_cand) ? a.g.cand_lo + j : -1;
-    const int pg = a.g.cand_lo + (j < a.g.n_cand ? j : 0);
-    if (ps < a.passes) {
-      wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
-      wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
+    for (int ps = 0; ps < SCORE_PASSES; ++ps) {
+      const int j = ch * pages_per_chunk + ps * PAGES_PER_PASS + wave * 4 + grp;
+      page[ps] = (ps < a.passes && j < a.g.n_cand) ? a.g.cand_lo + j : -1;
+      const int pg = a.g.cand_lo + (j < a.g.n_cand ? j : 0);
+      if (ps < a.passes) {
+        wmax[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 0, a.max_pages, pg) + c8 * 8);
+        wmin[ps] = *reinterpret_cast<const uint4*>(a.summ + summ_idx(b, m, a.n_kv, 1, a.max_pages, pg) + c8 * 8);
+      }
     }
-  }
+  };
+  load_chunk(chunk);
   float f[G][8];
 #pragma unroll
   for (int gg = 0; gg < G; ++gg) {
@@ -176,6 +179,9 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
   }
   const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
   float* const prow = a.P + (size_t)(b * a.n_q + m * G + (c8 < NG ? c8 : 0)) * a.max_pages;
+  // a block of a big scan takes every blocks_per_head-th chunk of its head, one after the other
+  for (int ch = chunk; ch * pages_per_chunk < a.g.n_cand; ch += a.blocks_per_head) {
+  if (ch != chunk) load_chunk(ch);
 #pragma unroll
   for (int ps = 0; ps < SCORE_PASSES; ++ps) {
     if (ps >= a.passes) break;
@@ -212,6 +218,7 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
     }
     // one store per pass: lane c8 of a page's 16 lanes writes the weight of query head c8
     if (c8 < NG && page[ps] >= 0) st_dev(prow + page[ps], mine * scale);
+  }
   }
 }
 

@@ -433,3 +433,14 @@ def test_many_requests_take_the_bandwidth_bound_dispatch():
     assert 0 < pr.stats["flagged"] < pr.stats["heads"]
     print("many", pr.stats)
     pr.close()
+
+
+def test_big_scan_blocks_take_several_chunks():
+    """24 requests x 16 KV heads x 12K tokens: the scoring launch is past the size where a block takes
+    several chunks of its head in turn (and 4 passes per chunk)."""
+    wl = W.Workload("scan", 1, 24, 16, 16, "bf16", 12000, 1024, 64, 64, 0.8, 3, 0.8, 0.6, 71)
+    pr = _pair(wl, [0])
+    for t in range(wl.steps):
+        pr.step(0, t)
+    assert pr.g.step_launches(0) == 3        # scoring, selection, attention
+    pr.close()
