@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the split attention kernel at this workload, from
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs scaled by a copy kernel of known
 # size (profiles/layer_step_c2_pmc.txt).  None until measured.
-MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9388800, "layer_kernel": 14052200}
+MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9396100, "layer_kernel": 14027600}
 
 
 def algorithmic_bytes(wl):
