@@ -444,3 +444,14 @@ def test_big_scan_blocks_take_several_chunks():
         pr.step(0, t)
     assert pr.g.step_launches(0) == 3        # scoring, selection, attention
     pr.close()
+
+
+def test_pooling_variants_with_the_host_pool():
+    """A selection variant together with max-pooled correction on the host-pool placement: the recall plan
+    follows whatever the variant selects."""
+    wl = W.get_workload("c3").scaled(batch=2, ctx=6000, steps=30)
+    pr = _pair(wl, [3], steps=30, select_pooling="MaxQK", corr_pooling="min")
+    for t in range(30):
+        pr.step(0, t)
+    assert pr.stats["misses"] > 0 and 0 < pr.stats["flagged"] < pr.stats["heads"]
+    pr.close()
