@@ -157,13 +157,14 @@ int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int
 
 /* ---- the loop's primitives --------------------------------------------- */
 
-/* Correction test (Sec. 3.1, 3.3): per KV head, 1 iff the group mean of
- * cos(q, q_prev) is < tau, or there is no previous query.  q dev [batch, n_q, d];
+/* Correction test (Sec. 3.1, 3.3): per KV head, 1 iff the group-pooled (cfg.corr_pooling;
+ * the method: mean) cos(q, q_prev) is < tau, or there is no previous query.  q dev [batch, n_q, d];
  * flags_dev (may be NULL) receives [batch, n_kv] bytes.  Also stages q as the
  * next step's q_prev; it becomes q_prev at fkv_commit. */
 int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flags_dev, void* stream);
 
-/* Sel(q) for every KV head (Sec. 3.2): scores candidate pages, picks the
+/* Sel(q) for every KV head (Sec. 3.2): scores candidate pages, pools the scores over the query
+ * group (cfg.select_pooling; the method: mean of the per-head softmax), picks the
  * k = (B-S-W)/p best (ties to the lower page id).  page_ids_dev (may be NULL)
  * receives [batch, n_kv, k] int32, ascending, padded with -1.  The result is
  * kept as the PENDING selection; for placement HOST the pages it misses in the
