@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the FreeKV retrieval-decode path on one MI355X.
 
-Workload (`config.workload`): the Llama-3-8B-shaped decode of the second BASELINE config --
+Workload (`config.workload`): the Llama-3-8B-shaped decode --
 32 layers, 32 query / 8 KV heads, head_dim 128, bf16, batch 1, 32768 cached tokens, page 32,
 budget 2048 (sink = window = 512), tau 0.8, step-correlated queries (rho = 0.9), KV resident
 in HBM.  One "step" is one decode step: fkv_decode_step for each of the 32 layers, i.e. every
@@ -9,7 +9,11 @@ row of the hot path (append + summary update, correction test, page weights, sof
 top-k, speculative reuse / correction, sparse attention) 32 times.  All inputs are generated
 on the GPU beforehand and are resident in HBM when the timed region starts.
 
-Prints one JSON line; see the field notes in the design doc.
+Prints one JSON line: `value` = layer-steps/s of the whole job; `roofline` = the layer kernel's
+algorithmic HBM bytes per launch over its average launch duration (HIP events on the launch stream)
+against the 8 TB/s peak, with the counter-measured traffic; `cpu_baseline` = the CPU oracle timed on
+one layer of the same workload; `config.saturated_shape` = the same shape with 32 requests, where the
+path is bound by bandwidth rather than by its chain of dependent memory round trips.
 """
 from __future__ import annotations
 
@@ -161,7 +165,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards over KV heads / requests "
-              "with no exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "with no exchange between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
