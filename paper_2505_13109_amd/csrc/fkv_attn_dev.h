@@ -346,6 +346,22 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
     }
     __syncthreads();
     if (split == 0) FKV_ASTAMP(23);
+    if (a.n_splits == 1) {
+      // the block has the whole head: normalise and write the output, no partial, no merge
+      for (int i = threadIdx.x; i < G * D / 2; i += NW * 64) {
+        const int gg = i / (D / 2), c = (i % (D / 2)) * 2;
+        float s0 = 0.0f, s1 = 0.0f, den = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          s0 += sm_o[((size_t)w * G + gg) * D + c];
+          s1 += sm_o[((size_t)w * G + gg) * D + c + 1];
+          den += sm_l[w * 16 + gg];
+        }
+        const float inv = 1.0f / den;
+        *reinterpret_cast<float2*>(a.out + (size_t)(b * n_q + m * G + gg) * D + c) = make_float2(s0 * inv, s1 * inv);
+      }
+      return;
+    }
     for (int i = threadIdx.x; i < G * D / 2; i += NW * 64) {
       const int gg = i / (D / 2), c = (i % (D / 2)) * 2;
       float s0 = 0.0f, s1 = 0.0f;

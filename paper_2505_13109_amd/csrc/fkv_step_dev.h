@@ -217,7 +217,11 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
       mine = c8 == gg ? s : mine;
     }
     // one store per pass: lane c8 of a page's 16 lanes writes the weight of query head c8
-    if (c8 < NG && page[ps] >= 0) st_dev(prow + page[ps], mine * scale);
+    // (device-scope only if a block of this launch is going to read it)
+    if (c8 < NG && page[ps] >= 0) {
+      if (a.fuse_select) st_dev(prow + page[ps], mine * scale);
+      else prow[page[ps]] = mine * scale;
+    }
   }
   }
 }
@@ -309,6 +313,12 @@ template <int U> struct UnrollBy { static constexpr int value = U; };
 #define FKV_SEL_MARK(i)
 #endif
 
+// a page weight: written earlier in this very launch by another block (device-scope read), or by a
+// launch that has ended (plain read)
+__device__ __forceinline__ float ld_weight(const float* p, bool same_launch) {
+  return same_launch ? ld_dev(p) : *p;
+}
+
 template <int G, bool STAGED, bool ROOMY>
 __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32_t* key) {
   __shared__ float s_redf[STEP_WAVES][G];
@@ -337,6 +347,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   const float* Pm = a.P + (size_t)(b * a.n_q + m * G) * a.max_pages + lo;
   uint32_t* pw = key + n;                              // [G][n]: weights, later their fixed-point softmax
   constexpr bool staged = STAGED;                      // else: re-read the weights from memory in each pass
+  const bool same_launch = a.select_only == 0;         // the weights come from scoring blocks of this launch
   const int mode = a.sel_pool;                         // FKV_POOL_*
   const bool soft = mode <= 1;                         // the variants that pool softmax values
   const int ng = mode >= 4 ? 1 : G;                    // rows of P in use (pooled query: the group's first)
@@ -354,7 +365,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
       const int j = min(tid + u * STEP_THREADS, n - 1);
 #pragma unroll
       for (int gg = 0; gg < G; ++gg)
-        e[u][gg] = gg < ng ? __float_as_uint(ld_dev(Pm + (size_t)gg * a.max_pages + j)) : 0u;
+        e[u][gg] = gg < ng ? __float_as_uint(ld_weight(Pm + (size_t)gg * a.max_pages + j, same_launch)) : 0u;
     }
     double zd[G];
 #pragma unroll
@@ -446,7 +457,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
       for (int u = 0; u < U; ++u) {
         const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
-        for (int gg = 0; gg < G; ++gg) v[u][gg] = gg < ng ? ld_dev(Pm + (size_t)gg * a.max_pages + j) : 0.0f;
+        for (int gg = 0; gg < G; ++gg) v[u][gg] = gg < ng ? ld_weight(Pm + (size_t)gg * a.max_pages + j, same_launch) : 0.0f;
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -493,7 +504,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
         const int j = min(j0 + u * STEP_THREADS, n - 1);
 #pragma unroll
         for (int gg = 0; gg < G; ++gg)
-          v[u][gg] = staged ? __uint_as_float(pw[gg * n + j]) : ld_dev(Pm + (size_t)gg * a.max_pages + j);
+          v[u][gg] = staged ? __uint_as_float(pw[gg * n + j]) : ld_weight(Pm + (size_t)gg * a.max_pages + j, same_launch);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -544,7 +555,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
       for (int gg = 0; gg < G; ++gg) {
         if (staged) e[u][gg] = pw[gg * n + j];
         else if (gg < ng) {
-          const float w = ld_dev(Pm + (size_t)gg * a.max_pages + j);
+          const float w = ld_weight(Pm + (size_t)gg * a.max_pages + j, same_launch);
           e[u][gg] = soft ? softmax_fixed(w, mx[gg]) : __float_as_uint(w);
         } else e[u][gg] = 0;
       }
