@@ -262,10 +262,23 @@ __device__ __forceinline__ float key_score(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
-// The correctly rounded fp64 quotient a / b from y = RN(1 / b) (one true division per head, not per
-// candidate): q = a * y is within 1.5 ulp; one correction with the exact remainder r = a - b * q makes
-// it faithful, and for a faithful q the same correction again returns RN(a / b) (Markstein's final
-// step).  0 <= a <= b < 2^48 are integers here; no over- or underflow.
+// A reciprocal of b good to an ulp or two: the hardware's approximation (a dozen bits would do)
+// sharpened by three Newton steps.
+__device__ __forceinline__ double reciprocal_near(double b) {
+  double y = __builtin_amdgcn_rcp(b);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const double e = __builtin_fma(-b, y, 1.0);
+    y = __builtin_fma(y, e, y);
+  }
+  return y;
+}
+
+// The correctly rounded fp64 quotient a / b of integers 0 <= a <= b < 2^48 from such a y (one
+// reciprocal per head, not one division per candidate): q = a * y corrected twice with the exact
+// remainder r = a - b * q.  After the first correction q is within an ulp; the second leaves an
+// error of at most |r| * |y - 1/b| <= 2^-52 ulp, and a / b with b < 2^48 is either representable or at
+// least 2^-49 ulp away from the nearest rounding boundary, so the rounding cannot go wrong.
 __device__ __forceinline__ double div_rn(double a, double b, double y) {
   double q = a * y;
   double r = __builtin_fma(-b, q, a);
@@ -423,7 +436,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     }
     double zr[G];
 #pragma unroll
-    for (int gg = 0; gg < G; ++gg) zr[gg] = 1.0 / zd[gg];
+    for (int gg = 0; gg < G; ++gg) zr[gg] = reciprocal_near(zd[gg]);
     FKV_SEL_MARK(2);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -540,7 +553,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   }
   double zr[G];
 #pragma unroll
-  for (int gg = 0; gg < G; ++gg) zr[gg] = 1.0 / zd[gg];
+  for (int gg = 0; gg < G; ++gg) zr[gg] = reciprocal_near(zd[gg]);
   FKV_SEL_MARK(2);
   // pooled score of each candidate (each thread reads back only what it wrote); the top
   // byte of its key goes straight into the first histogram
