@@ -397,7 +397,10 @@ def main():
     del kv, q, k_new, v_new, out
     torch.cuda.empty_cache()
     if args.saturation_batch > 0 and wl.name == "c2" and args.batch == 0 and not args.real_layer and not args.standin_mb:
-        res["config"]["saturated_shape"] = saturated_rate(torch, fkv, wl, args.saturation_batch)
+        try:                             # a side measurement: it must not cost the line above
+            res["config"]["saturated_shape"] = saturated_rate(torch, fkv, wl, args.saturation_batch)
+        except Exception as e:           # noqa: BLE001
+            res["config"]["saturated_shape"] = {"error": f"{type(e).__name__}: {e}"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))
