@@ -455,3 +455,19 @@ def test_pooling_variants_with_the_host_pool():
         pr.step(0, t)
     assert pr.stats["misses"] > 0 and 0 < pr.stats["flagged"] < pr.stats["heads"]
     pr.close()
+
+
+def test_host_pool_fp16_ragged_growth():
+    """fp16, G = 5, two requests, host pool, context growing from 40 tokens through page fills (offloads),
+    the first candidates and the first recalls."""
+    wl = W.Workload("hostgrow", 1, 2, 10, 2, "fp16", 40, 256, 32, 64, 0.75, 260, 0.75, 0.66, 81, placement=1, shift_every=70)
+    pr = _pair(wl, [4])
+    for t in range(wl.steps):
+        pr.step(0, t, deep=(t % 5 == 0))
+        if t % 64 == 63:
+            torch.cuda.synchronize()
+            pr.check_cached_pages(0, 1, 1, where=1)
+            pr.check_cached_pages(0, 0, 0, where=2)
+    assert pr.stats["misses"] > 0 and 0 < pr.stats["flagged"] < pr.stats["heads"]
+    print("hostgrow", pr.stats)
+    pr.close()
