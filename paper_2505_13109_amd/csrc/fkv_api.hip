@@ -95,6 +95,7 @@ const char* check_config(const fkv_config* c) {
   if (c->placement != FKV_PLACE_HBM && c->placement != FKV_PLACE_HOST) return "bad placement";
   if ((size_t)(c->max_ctx / PG) * 4 + 4096 > 65536) return "max_ctx above 491520 tokens is not supported (top-k keys live in LDS)";
   if ((c->budget_tokens - c->sink_tokens - c->window_tokens) / PG > 1024) return "more than 1024 selectable pages are not supported";
+  if (c->placement == FKV_PLACE_HOST && (long)c->batch * c->n_kv_heads > 16384) return "more than 16384 (request, KV head) pairs are not supported with the host pool";
   if (c->tau != c->tau) return "tau is NaN";
   if (c->recall_mode != FKV_RECALL_GATHER && c->recall_mode != FKV_RECALL_MEMCPY) return "bad recall_mode";
   if (c->select_pooling < FKV_POOL_MEAN_S || c->select_pooling > FKV_POOL_MAX_Q) return "bad select_pooling";

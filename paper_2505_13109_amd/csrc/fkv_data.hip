@@ -108,34 +108,49 @@ __global__ __launch_bounds__(256) void offload_kernel(PoolDesc pd, uint16_t* __r
 
 // ---- recall: copy missing pages host pool -> free page-cache slots ---------------
 // miss: [heads][1 + 2k] = count, then k page ids, then k slots.
-// A few 1024-thread blocks walk the miss lists, four 16 KiB units in flight per block.  Loads
+// A few 1024-thread blocks share the miss lists, four 16 KiB units in flight per block.  Loads
 // from host memory take microseconds to return and hold up the memory pipeline of the compute
 // unit they are issued from, so the blocks are kept few and each one claims a whole compute
 // unit's LDS: no block of a kernel that uses LDS (attention, scoring) can share that unit.
 constexpr int GATHER_THREADS = 1024;
+constexpr int GATHER_BLOCKS = 16;            // measured: 8 and 16 blocks move 52-53 GB/s, 24 blocks 50, 32 blocks 47
+constexpr int GATHER_UNITS = 4;              // units in flight per block (8 is no faster)
 __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, const uint16_t* __restrict__ host_pool,
                                                                 const int32_t* __restrict__ miss,
                                                                 const uint8_t* __restrict__ flags, int heads_mode,
                                                                 int k, int n_kv, int n_heads, int max_pages) {
+  extern __shared__ int32_t chunks_of[];     // [n_heads]: 4-unit chunks this launch moves for each head
   const int tid = threadIdx.x;
-  for (int head = blockIdx.x; head < n_heads; head += gridDim.x) {
-    if (heads_mode != 0) {
-      const bool flagged = flags[head] != 0;
-      if ((heads_mode == 1) != flagged) continue;
-    }
+  // The chunks (GATHER_UNITS units each) of all chosen heads, numbered through, are dealt to the blocks in turn, so that every
+  // block moves the same amount whatever the heads' miss counts are (a corrected-heads launch
+  // serves about every other head, with anything from 0 to k misses).
+  for (int head = tid; head < n_heads; head += GATHER_THREADS) {
+    const bool chosen = heads_mode == 0 || ((heads_mode == 1) == (flags[head] != 0));
+    chunks_of[head] = chosen ? (miss[(size_t)head * (1 + 2 * k)] + GATHER_UNITS - 1) / GATHER_UNITS : 0;
+  }
+  __syncthreads();
+  int first = 0;                                // number of the head's first chunk
+  for (int head = 0; head < n_heads; ++head) {
+    const int n_chunks = chunks_of[head];
+    const int c_begin = first;
+    first += n_chunks;
+    // chunks of this head that are this block's: c_begin + j with (c_begin + j) % gridDim.x == blockIdx.x
+    int j = ((int)blockIdx.x - c_begin % (int)gridDim.x + (int)gridDim.x) % (int)gridDim.x;
+    if (j >= n_chunks) continue;
     const int32_t* mh = miss + (size_t)head * (1 + 2 * k);
     const int n = mh[0];
     const uint16_t* src_head = host_pool + (size_t)head * max_pages * UNIT_ELEMS;
     uint16_t* dst_head = pd.pool + ((size_t)head * pd.units_per_head + pd.sel_base) * UNIT_ELEMS;
-    for (int i0 = 0; i0 < n; i0 += 4) {
-      uint4 w[4];
+    for (; j < n_chunks; j += gridDim.x) {
+      const int i0 = j * GATHER_UNITS;
+      uint4 w[GATHER_UNITS];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < GATHER_UNITS; ++u) {
         const int i = min(i0 + u, n - 1);
         w[u] = reinterpret_cast<const uint4*>(src_head + (size_t)mh[1 + i] * UNIT_ELEMS)[tid];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < GATHER_UNITS; ++u) {
         if (i0 + u < n) reinterpret_cast<uint4*>(dst_head + (size_t)mh[1 + k + i0 + u] * UNIT_ELEMS)[tid] = w[u];
       }
     }
@@ -270,7 +285,7 @@ void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool,
     raised = true;
   }
   const int n_heads = d.batch * d.n_kv;
-  const int blocks = n_heads < 16 ? n_heads : 16;
+  const int blocks = n_heads < GATHER_BLOCKS ? n_heads : GATHER_BLOCKS;
   gather_kernel<<<blocks, GATHER_THREADS, hog, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, n_heads, d.max_pages);
 }
 

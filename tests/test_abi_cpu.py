@@ -48,7 +48,7 @@ def test_arena_bytes_and_config_checks():
     for bad in (dict(head_dim=64), dict(page_size=16), dict(n_q_heads=30), dict(n_q_heads=128),
                 dict(max_ctx=100), dict(budget_tokens=48), dict(dtype=3), dict(placement=2),
                 dict(sink_tokens=40), dict(n_layers=0), dict(recall_mode=7), dict(select_pooling=6),
-                dict(select_pooling=-1), dict(corr_pooling=3)):
+                dict(select_pooling=-1), dict(corr_pooling=3), dict(placement=1, batch=4096)):
         assert L.fkv_arena_bytes(C.byref(_cfg(**bad)), C.byref(dev), C.byref(host)) == -1, bad
         assert L.fkv_last_error(None)
 
