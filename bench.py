@@ -181,8 +181,6 @@ def main():
               "with no exchange between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import torch
-    import paper_2505_13109_amd as fkv
     import workloads as W
 
     wl = W.get_workload(args.workload)
@@ -201,6 +199,9 @@ def main():
             cpu = cpu_baseline(wl)
         except Exception as e:               # noqa: BLE001 - a side measurement must not cost the result line
             cpu = {"value": None, "unit": "layer-steps/s", "cores": 0, "kind": "oracle", "sample": f"failed: {type(e).__name__}: {e}"}
+
+    import torch                             # after the fork: the workers carry no torch threads
+    import paper_2505_13109_amd as fkv
     if args.calibration_copy:
         a = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda:0")
         for _ in range(3):
