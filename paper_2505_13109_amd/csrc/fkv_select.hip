@@ -1,6 +1,7 @@
-// The "step" kernel: one launch that appends the token, runs the correction test, scores the
-// candidate pages and (by the last scoring block of each KV head) selects the top-k.
-// The roles themselves are in fkv_step_dev.h.
+// The "step" kernel (token append, correction test, page weights, and -- in its last scoring
+// block per KV head or in a launch of its own -- the top-k selection), the one-launch layer kernel
+// (the step roles plus the attention blocks), and the host-side rules that size their launches.
+// The roles themselves are in fkv_step_dev.h, attention in fkv_attn_dev.h.
 #include "fkv_step_dev.h"
 #include "fkv_attn_dev.h"
 #include <cstdlib>
@@ -35,9 +36,9 @@ static bool raise_lds(size_t lds) {
 }
 
 // The selection's LDS (keys + staged weights) is allocated for every block of a launch.  When
-// it is small the selection rides in the scoring launch (its last block per head runs it);
-// when it would limit how many scoring blocks fit a compute unit, scoring runs without it and
-// a second launch of one block per head selects.
+// it is small and the launch is at most one round of blocks, the selection rides in the scoring
+// launch (its last block per head runs it); otherwise scoring runs without it and a second
+// launch of one block per head selects.
 constexpr size_t kLdsPerUnit = 150 * 1024;   // of the 160 KiB of a compute unit
 constexpr int kComputeUnits = 256;
 constexpr int kFuseMaxBlocks = kComputeUnits;       // launches up to this size run the selection in their last scoring blocks

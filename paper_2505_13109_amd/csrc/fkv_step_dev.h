@@ -15,7 +15,8 @@
 //            degree-6 Horner in f with separate multiply and add; ldexp(., n);
 //            0 below t < -64; E = rint(e * 2^31) as integer; Z = integer sum of E;
 //   pooling: fl32( (sum_g fp64(E_g) / fp64(Z_g), g ascending) / fp64(G) ); the quotients are the
-//            correctly rounded ones, computed from RN(1/Z_g) with fused multiply-add corrections;
+//            correctly rounded ones, computed from a reciprocal of Z_g with fused multiply-add
+//            corrections (see div_rn);
 //            (alternatives, App. B.2: fl32(max_g E_g / Z_g); the fp32 sum of the weights in head
 //            order divided by G, or their maximum; the weight of the group's mean or maximum query)
 //   top-k:   radix select on the order-preserving image of the fp32 bit pattern, ties to the
