@@ -248,9 +248,10 @@ __device__ __forceinline__ uint32_t softmax_fixed(float p, float mx) {
   r = r * f; r = r + 0x1.ebfbep-3f;
   r = r * f; r = r + 0x1.62e43p-1f;
   r = r * f; r = r + 1.0f;
-  float e = __builtin_ldexpf(r, (int)n);
-  if (t < -64.0f) e = 0.0f;
-  return (uint32_t)__builtin_rintf(e * 2147483648.0f);
+  // e = ldexp(r, n) is exact here (n >= -64), and so is e * 2^31: one ldexp gives the same number
+  float e31 = __builtin_ldexpf(r, (int)n + 31);
+  if (t < -64.0f) e31 = 0.0f;
+  return (uint32_t)__builtin_rintf(e31);
 }
 
 // Scores can be negative in the variants that pool the weights themselves: map the fp32 bit
