@@ -471,3 +471,30 @@ def test_host_pool_fp16_ragged_growth():
     assert pr.stats["misses"] > 0 and 0 < pr.stats["flagged"] < pr.stats["heads"]
     print("hostgrow", pr.stats)
     pr.close()
+
+
+def test_a_seeded_sample_of_small_shapes():
+    """Forty shapes drawn from a seeded generator: group size, heads, requests, budget / sink / window,
+    context length, dtype, placement, pooling variants; 24 steps each, every step compared."""
+    rng = np.random.default_rng(2025)
+    for i in range(40):
+        G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
+        n_kv = int(rng.choice([1, 2, 3, 4]))
+        batch = int(rng.choice([1, 1, 2, 3]))
+        sink = int(rng.choice([0, 32, 64, 128]))
+        window = int(rng.choice([0, 32, 64, 96]))
+        k = int(rng.choice([1, 2, 5, 9, 16]))
+        ctx = int(rng.integers(1, 2600))
+        dtype = str(rng.choice(["bf16", "fp16"]))
+        placement = int(rng.choice([0, 0, 1]))
+        sp = str(rng.choice(["MeanS", "MeanS", "MaxS", "MeanQK", "MaxQK", "MeanQ", "MaxQ"]))
+        cp = str(rng.choice(["mean", "mean", "max", "min"]))
+        tau = float(rng.choice([0.6, 0.75, 0.85]))
+        wl = W.Workload(f"rand{i}", 1, batch, G * n_kv, n_kv, dtype, ctx, sink + window + 32 * k, sink, window, tau, 24,
+                        0.8, 0.6, 300 + i, placement=placement, shift_every=11)
+        tag = f"shape {i}: G {G} n_kv {n_kv} batch {batch} S {sink} W {window} k {k} ctx {ctx} {dtype} placement {placement} {sp}/{cp} tau {tau}"
+        print(tag, flush=True)
+        pr = _pair(wl, [i], select_pooling=sp, corr_pooling=cp)
+        for t in range(wl.steps):
+            pr.step(0, t)
+        pr.close()
