@@ -498,3 +498,24 @@ def test_a_seeded_sample_of_small_shapes():
         for t in range(wl.steps):
             pr.step(0, t)
         pr.close()
+
+
+def test_selection_paths_of_the_separate_step_kernel():
+    """The host-pool placement always takes the separate step kernel.  Candidate counts on both sides of its
+    register / LDS-staging thresholds, for small and large groups, with the selection inside the scoring
+    launch (few blocks) and in a launch of its own (many blocks)."""
+    shapes = [  # (G, n_kv, batch, ctx): n_cand = ctx/32 - 4
+        (8, 1, 1, 30000),     # 933 candidates, G > 4: in registers, 2 per thread
+        (8, 1, 1, 50000),     # 1558 candidates, G > 4: staged in LDS
+        (3, 2, 1, 50000),     # 1558 candidates, G <= 4: in registers, 4 per thread
+        (4, 2, 2, 90000),     # 2808 candidates: staged in LDS, selection in its own launch
+        (6, 2, 3, 20000),     # 621 candidates: 2 per thread
+    ]
+    for i, (G, n_kv, batch, ctx) in enumerate(shapes):
+        wl = W.Workload(f"sel{i}", 1, batch, G * n_kv, n_kv, "bf16", ctx, 1024, 64, 64, 0.8, 5, 0.8, 0.6, 400 + i, placement=1)
+        print(wl.name, G, n_kv, batch, ctx, flush=True)
+        pr = _pair(wl, [i])
+        for t in range(wl.steps):
+            pr.step(0, t)
+        assert pr.stats["misses"] > 0
+        pr.close()
