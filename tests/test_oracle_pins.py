@@ -535,3 +535,83 @@ def test_nhd_pool_holds_exactly_the_attended_tokens():
             sc = ks @ q[h].astype(np.float64) / math.sqrt(128)
             w = np.exp(sc - sc.max()); w /= w.sum()
             np.testing.assert_allclose(w @ vs, ref[h], rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- Sec. 3.2: the picked page SET against the plain definition
+def _plain_fp64_selection(o, q):
+    """Sel(q) written straight from Sec. 3.2 "Group-consistent selection" in fp64 with library routines:
+    page weight = sum_c max(q_c kmax_c, q_c kmin_c) / sqrt(d), softmax over the candidate pages (np.exp,
+    np.sum), mean over the group, the k best by (score descending, page id ascending).  Shares nothing
+    with the oracle's fixed-order fp32 / fixed-point arithmetic.  Returns ids (sets) and the scores."""
+    g = o.geom()
+    lo, hi = g.cand_lo, g.cand_lo + g.n_cand
+    q64 = q.astype(np.float64)
+    picked, scores = [], []
+    for m in range(o.n_kv):
+        kx, kn = o.kmax[lo:hi, m, :].astype(np.float64), o.kmin[lo:hi, m, :].astype(np.float64)
+        acc = np.zeros(g.n_cand)
+        for gq in range(o.G):
+            qh = q64[m * o.G + gq]
+            w = np.maximum(qh * kx, qh * kn).sum(axis=1) / math.sqrt(o.d)
+            e = np.exp(w - w.max())
+            acc += e / e.sum()
+        acc /= o.G
+        order = np.lexsort((np.arange(g.n_cand), -acc))[:g.k_eff]
+        picked.append(set((order + lo).tolist()))
+        scores.append(acc)
+    return picked, scores
+
+
+PAGE_SET_EPS = 2e-5   # relative; the contract's fp32 weights (a few ulp of ~20) and the exponential (2.5e-6) stay well inside it
+PAGE_SET_QUANTUM = 2.0 ** -31   # absolute; a head's softmax numerators are integers in units of 2^-31 of its largest one
+
+
+def _page_set_disagreements(o, q):
+    """Pages on which the oracle's Sel(q) and the plain fp64 selection differ, after asserting that every
+    such page is a numerical near-tie: its fp64 score within PAGE_SET_EPS (relative) plus one fixed-point
+    quantum of the k-th best."""
+    ids, _, _ = o.select(q)
+    plain, scores = _plain_fp64_selection(o, q)
+    g = o.geom()
+    n_diff = 0
+    for m in range(o.n_kv):
+        mine = {int(j) for j in ids[m] if j >= 0}
+        assert len(mine) == len(plain[m]) == g.k_eff
+        kth = np.sort(scores[m])[::-1][g.k_eff - 1]
+        for page in mine ^ plain[m]:
+            gap = abs(scores[m][page - g.cand_lo] - kth)
+            assert gap <= PAGE_SET_EPS * kth + PAGE_SET_QUANTUM, f"head {m} page {page}: fp64 score {scores[m][page - g.cand_lo]:.9e} vs k-th {kth:.9e}"
+            n_diff += 1
+    return n_diff
+
+
+def test_selected_page_set_equals_the_plain_fp64_definition_except_at_near_ties(capsys):
+    """The arithmetic contract (one fp32 summation order, a polynomial exponential, integer softmax sums)
+    must pick the pages the plain fp64 softmax-mean top-k picks, except where fp64 itself sees a near-tie.
+    C1's inputs (every step's query), the C2 shape at its full 32K context (one layer, several steps), and a
+    peaked case (queries scaled x16: the k-th best page then holds 1e-7 .. 1e-4 of a head's attention mass,
+    far down the softmax tail, where a cut-off or a dropped low-order term of the exponential would show;
+    scaled x32 the boundary falls below the 2^-31 quantum of the integer softmax and scores tie at zero)."""
+    total = picks = 0
+    wl = W.get_workload("c1")
+    (K, _), (V, _) = W.kv_prefix(wl, 0, 0)
+    o = O.FreeKVOracle(wl.n_q_heads, wl.n_kv_heads, 128, 32, wl.budget, wl.sink, wl.window, wl.tau, wl.max_ctx)
+    o.load_prefix_bulk(K, V)
+    q, _ = W.query_stream(wl, 0, 0)
+    for t in range(0, wl.steps, 3):
+        total += _page_set_disagreements(o, q[t]); picks += wl.n_kv_heads * o.geom().k_eff
+    wl = W.get_workload("c2")
+    (K, _), (V, _) = W.kv_prefix(wl, 3, 0)
+    o = O.FreeKVOracle(wl.n_q_heads, wl.n_kv_heads, 128, 32, wl.budget, wl.sink, wl.window, wl.tau, wl.max_ctx)
+    o.load_prefix_bulk(K, V)
+    q, _ = W.query_stream(wl, 3, 0, 12)
+    assert o.geom().n_cand == 992 and o.geom().k_eff == 32
+    for t in range(12):
+        total += _page_set_disagreements(o, q[t]); picks += wl.n_kv_heads * 32
+        qs = W.decode(W.encode(q[t] * np.float32(16.0), wl.dtype), wl.dtype)
+        _, scores = _plain_fp64_selection(o, qs)
+        assert min(np.sort(s)[::-1][31] for s in scores) < 1e-6          # the boundary is deep in the tail
+        total += _page_set_disagreements(o, qs); picks += wl.n_kv_heads * 32
+    with capsys.disabled():
+        print(f"\n[page-set pin] {total} near-tie disagreements with the plain fp64 selection in {picks} picks")
+    assert total <= picks // 1000

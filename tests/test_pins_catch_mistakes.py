@@ -20,7 +20,7 @@ def _pin_calls():
             continue
         marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
         if not marks:
-            calls.append((name, fn))
+            calls.append((name, _call_page_set_pin if name == PAGE_SET_PIN else fn))
             continue
         argnames = [a.strip() for a in marks[0].args[0].split(",")]
         for values in marks[0].args[1]:
@@ -36,6 +36,19 @@ def _first_failing_pin():
         except Exception:                 # noqa: BLE001 - any failure of a pin counts
             return name
     return None
+
+
+def _all_failing_pins():
+    failing = []
+    for name, call in _pin_calls():
+        try:
+            call()
+        except Exception:                 # noqa: BLE001
+            failing.append(name)
+    return failing
+
+
+PAGE_SET_PIN = "test_selected_page_set_equals_the_plain_fp64_definition_except_at_near_ties"
 
 
 def test_the_pins_pass_on_the_oracle_as_it_is():
@@ -172,6 +185,7 @@ MODULE_MISTAKES = {
     "mean query divided by n_q instead of G": ("pool_queries", _pool_queries_wrong_divisor),
 }
 _orig = {name: getattr(O, name) for name, _ in MODULE_MISTAKES.values()}
+_orig["exp_spec"] = O.exp_spec
 
 
 @pytest.mark.parametrize("mistake", sorted(MODULE_MISTAKES))
@@ -205,6 +219,51 @@ def _attended_without_open_page(self, page_ids):
 def _export_nhd_kv_swapped(self, ids, n_slots):
     pool, pages = _orig_export(self, ids, n_slots)
     return pool[:, ::-1].copy(), pages
+
+
+def _exp_cut_off_too_early(x):
+    x = np.asarray(x, dtype=F32)
+    e = _orig["exp_spec"](x)
+    return np.where(x * O.LOG2E_F32 < F32(-20.0), F32(0.0), e)
+
+
+def test_an_early_exponential_cut_off_changes_the_picked_page_set(monkeypatch):
+    """The cut-off of the exponential moved from t < -64 to t < -20: in a peaked softmax the k-th best page
+    lies below it, the tail ties at zero and the picked SET departs from the plain fp64 definition."""
+    monkeypatch.setattr(O, "exp_spec", _exp_cut_off_too_early)
+    with pytest.raises(AssertionError):
+        _call_page_set_pin()
+
+
+def _call_page_set_pin():
+    class _NoCapture:                      # stands in for pytest's capsys fixture
+        def disabled(self):
+            import contextlib
+            return contextlib.nullcontext()
+    getattr(pins, PAGE_SET_PIN)(_NoCapture())
+
+
+def _select_softmax_over_every_page(self, q):
+    """Sel(q) with the softmax normalised over ALL full pages (sink and window included) instead of the
+    candidate pages only; the top-k still runs over the candidates."""
+    g = self.geom()
+    lo, hi = g.cand_lo, g.cand_lo + g.n_cand
+    P_all = O.page_weights(q, self.kmax[:g.n_full], self.kmin[:g.n_full])
+    score = O.pooled_scores(P_all, self.G, self.select_pooling)[:, lo:hi]
+    ids = np.full((self.n_kv, self.k), -1, dtype=np.int32)
+    for m in range(self.n_kv):
+        top = O.topk_pages(score[m], g.k_eff)
+        ids[m, :top.shape[0]] = top + lo
+    return ids, P_all[:, lo:hi], score
+
+
+def test_softmax_over_sink_and_window_pages_is_caught_by_the_page_set_pin_alone(monkeypatch):
+    """A mistake in WHICH pages enter the softmax moves every head's normaliser by its own amount, which
+    re-weights the heads inside the group mean: value-level pins on pooled_scores cannot see it (the function
+    is handed the wrong rows but computes them correctly); only the comparison of the picked set with the
+    plain definition does."""
+    monkeypatch.setattr(O.FreeKVOracle, "select", _select_softmax_over_every_page)
+    assert _all_failing_pins() == [PAGE_SET_PIN]
 
 
 _orig_step, _orig_attended, _orig_export = O.FreeKVOracle.step, O.FreeKVOracle.attended_tokens, O.FreeKVOracle.export_nhd
