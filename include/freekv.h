@@ -80,7 +80,7 @@ extern "C" {
 #define FKV_USE_PENDING  1  /* pages picked at this step                           */
 #define FKV_USE_BY_FLAG  2  /* per KV head: pending if its correction flag is set  */
 
-/* which KV heads fkv_recall_pages serves */
+/* which KV heads fkv_recall_pending serves */
 #define FKV_HEADS_ALL        0
 #define FKV_HEADS_FLAGGED    1
 #define FKV_HEADS_UNFLAGGED  2
@@ -124,10 +124,10 @@ int fkv_context_len(const fkv_ctx* ctx, int32_t layer);
 
 /* Did every kernel of `layer` so far finish its bounded waits?  In the one-launch layer-step the
  * attention blocks of a corrected head wait for that head's selection, made by other blocks of the
- * same launch; the wait is bounded (about 0.1 s), and a block that gives up sets a flag and goes on
- * with whatever page ids it finds.  That is not expected to happen; this call synchronises the
- * device, returns FKV_ETIMEOUT if it did (the layer's outputs since the previous call are then not
- * to be trusted) and clears the flag.  Blocking. */
+ * same launch; the wait is bounded (about 0.1 s).  A block that gives up makes the failure visible
+ * on the data path -- every output row of that KV head's query group is NaN -- and sets a flag.
+ * That is not expected to happen; this call synchronises the device, returns FKV_ETIMEOUT if it did
+ * and clears the flag.  Blocking. */
 int fkv_health(fkv_ctx* ctx, int32_t layer);
 
 /* Kernel launches the last fkv_decode_step of `layer` put on the compute stream: 1 when the
@@ -150,8 +150,10 @@ int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* 
 int fkv_kv_append(fkv_ctx* ctx, int32_t layer, const void* k_new_dev, const void* v_new_dev,
                   void* stream, void* copy_stream);
 
-/* Recompute the summaries of pages [first_page, first_page + n_pages) from the
- * stored keys (placement HBM only). */
+/* Recompute the min-max summaries (channel-wise maximum and minimum of a page's keys, Sec. 3.2
+ * "Group-consistent selection") of pages [first_page, first_page + n_pages) from the stored keys;
+ * a partial last page is summarised over the tokens it holds.  Placement HBM only (FKV_ESTATE
+ * otherwise: the keys are not on the GPU); FKV_ERANGE if the range reaches past the cached context. */
 int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int32_t n_pages,
                             void* stream);
 
@@ -171,10 +173,27 @@ int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flag
  * GPU page cache are worked out too. */
 int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* page_ids_dev, void* stream);
 
-/* Placement HOST: copy the PENDING selection's missing pages of the chosen
- * heads (FKV_HEADS_*) from the host pool into free slots of the GPU page cache.
- * Slots read by the ACTIVE selection are never written.  Placement HBM: no-op. */
-int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream);
+/* Recall (Sec. 4.1: the data plane moves picked pages from the CPU pool into the GPU cache of selected
+ * pages; Sec. 4.2: one contiguous block of 2*p*d elements per (page, KV head)).  Placement HOST; a
+ * no-op returning 0 for placement HBM.
+ *   page_ids_dev  dev [batch, n_kv, k] int32 or NULL.  A list: ascending, distinct, -1 padded at the end
+ *                 (what fkv_page_select emits); it becomes the PENDING selection, as if selected.  Entries
+ *                 that are not a full page of the context (negative, or >= context_len / p) are dropped
+ *                 (set to -1) on the device, so no address is ever formed from them; an unsorted list only
+ *                 costs extra copies.  NULL: the PENDING selection made by fkv_page_select.
+ *   head_mask_dev dev [batch, n_kv] bytes or NULL: recall only for heads whose byte is non-zero (NULL = all).
+ * Pages of the list that the ACTIVE selection already holds keep their slot and are not copied; the
+ * others go to slots that the ACTIVE selection does not reference, so attention on ACTIVE may run
+ * beside it.  Everything is enqueued on copy_stream (cfg.recall_mode MEMCPY: blocks on it once);
+ * attention on the PENDING selection has to be ordered behind it by the caller (same stream or an
+ * event).  FKV_ESTATE with NULL ids before any fkv_page_select. */
+int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, const int32_t* page_ids_dev, const uint8_t* head_mask_dev,
+                     void* copy_stream);
+
+/* The same for the PENDING selection with the heads chosen by the correction flags (Sec. 3.3:
+ * corrected heads are recalled before this step's attention, the others afterwards, for the next
+ * step): heads = FKV_HEADS_*.  This is what fkv_decode_step issues. */
+int fkv_recall_pending(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream);
 
 /* o_h = softmax(q_h K^T / sqrt(d)) V over sink + picked pages + window + open
  * page (Sec. 2.1), the group sharing its KV head's pages.  `use` = FKV_USE_*.
@@ -196,7 +215,12 @@ int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float
 int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev, int32_t* slot_pages_dev,
                    int32_t n_slots, void* stream);
 
-/* End of step: PENDING becomes ACTIVE, the staged query becomes q_prev (host-side flip). */
+/* End of step (Sec. 3.3: by the end of a step every KV head's Sel(q_i) has been recalled -- corrected
+ * heads before attention, the others deferred -- and is what step i+1 reuses): PENDING becomes ACTIVE,
+ * the staged query becomes q_prev.  Host-side flip of two buffer halves, nothing is enqueued.
+ * FKV_ESTATE unless fkv_corr_check and fkv_page_select (or fkv_recall_pages with a list) ran since the
+ * last commit, and, for placement HOST, unless the pending pages of every head were recalled (a recall
+ * with a head mask does not count): the page cache would otherwise hold slots that were never filled. */
 int fkv_commit(fkv_ctx* ctx, int32_t layer);
 
 /* One whole step of one layer in the order of Sec. 3.2-3.3:
@@ -207,28 +231,6 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer);
 int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev,
                     const void* v_new_dev, float* out_dev, void* compute_stream, void* copy_stream);
 
-/* ---- per-kernel timers ---------------------------------------------------- */
-/* Time the split attention kernel (the dominant HBM reader of the step) with a
- * HIP event pair around each of the next max_launches launches, on the stream it
- * is launched on.  max_launches = 0 switches the timers off.  Blocking. */
-int fkv_profile_enable(fkv_ctx* ctx, int32_t max_launches);
-/* Sum of the recorded durations (ms) and their number; resets the timers.  Blocking. */
-int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches);
-
-/* Launch the attention kernel `reps` times for every layer in turn (ACTIVE selection, the
- * state is not changed), back to back on `stream` between one HIP event pair, and return
- * the elapsed time and the number of launches.  q_dev: layer l's queries at
- * q_dev + l * q_layer_stride bytes.  out_dev: [batch, n_q, d] fp32 scratch output.  Blocking. */
-int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, float* out_dev, int32_t reps,
-                     void* stream, double* total_ms, int32_t* launches);
-
-/* The cost of a launch as such: `reps` launches, back to back on `stream` between one HIP event
- * pair, of a kernel with the grid, block size and dynamic LDS of `layer`'s last one-launch
- * layer-step whose blocks return at once.  FKV_ESTATE if that step took several launches.
- * grid / lds_bytes (may be NULL) receive the shape.  Blocking. */
-int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* stream, double* total_ms,
-                             int32_t* grid, int32_t* lds_bytes);
-
 /* ---- introspection for tests (blocking: synchronises the device) --------- */
 #define FKV_DBG_SUMMARIES   0  /* T     [batch, n_kv, 2 (max,min), max_pages, d]      */
 #define FKV_DBG_WEIGHTS     1  /* f32   [batch, n_q, max_pages]  page weights P        */
@@ -238,13 +240,13 @@ int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* st
 #define FKV_DBG_FLAGS       5  /* u8    [batch, n_kv]                                  */
 #define FKV_DBG_MISS        6  /* i32   [batch, n_kv, 1 + k]: count, then page ids     */
 #define FKV_DBG_COSINE      7  /* f64   [batch, n_q]                                   */
-#define FKV_DBG_TSTAMP      8  /* i64   [64] 100 MHz phase timestamps of head 0, recorded when the
-                                  context was created with FKV_TSTAMP=1 in the environment     */
+#define FKV_DBG_TSTAMP      8  /* i64   [64] 100 MHz phase timestamps of head 0, recorded while
+                                  fkv_instrument_timestamps (freekv_instrument.h) is on         */
 int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes);
 
 /* Token-major copy of one page of one (request, KV head): host_out receives
  * K [p, d] then V [p, d] (2*p*d elements of T).  where: 0 = the HBM store
- * (placement HBM), 1 = the host pool, 2 = the GPU page-cache slot the ACTIVE
+ * (placement HBM), 1 = the host pool, 2 / 3 = the GPU page-cache slot the ACTIVE / PENDING
  * selection holds `page` in (error if it is not picked). */
 int fkv_debug_read_page(fkv_ctx* ctx, int32_t layer, int32_t request, int32_t kv_head,
                         int32_t page, int32_t where, void* host_out);

@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
     "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
+    "fkv_recall_pending", "fkv_test_lose_selection", "fkv_instrument_timestamps",
 )
 
 
@@ -77,7 +78,10 @@ def lib() -> C.CDLL:
         "fkv_page_summary_update": (C.c_int, [vp, i32, i32, i32, vp]),
         "fkv_corr_check": (C.c_int, [vp, i32, vp, vp, vp]),
         "fkv_page_select": (C.c_int, [vp, i32, vp, vp, vp]),
-        "fkv_recall_pages": (C.c_int, [vp, i32, i32, vp]),
+        "fkv_recall_pages": (C.c_int, [vp, i32, vp, vp, vp]),
+        "fkv_recall_pending": (C.c_int, [vp, i32, i32, vp]),
+        "fkv_test_lose_selection": (C.c_int, [vp, i32]),
+        "fkv_instrument_timestamps": (C.c_int, [vp, i32]),
         "fkv_sparse_decode_attn": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_commit": (C.c_int, [vp, i32]),
         "fkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
@@ -184,8 +188,17 @@ class FreeKV:
     def page_select(self, layer, q, page_ids=None, stream=None):
         self._check(self.L.fkv_page_select(self._h, layer, _ptr(q), _ptr(page_ids), _stream(stream)), "fkv_page_select")
 
-    def recall_pages(self, layer, heads=FKV_HEADS_ALL, copy_stream=None):
-        self._check(self.L.fkv_recall_pages(self._h, layer, heads, _stream(copy_stream)), "fkv_recall_pages")
+    def recall_pages(self, layer, page_ids=None, head_mask=None, copy_stream=None):
+        self._check(self.L.fkv_recall_pages(self._h, layer, _ptr(page_ids), _ptr(head_mask), _stream(copy_stream)), "fkv_recall_pages")
+
+    def recall_pending(self, layer, heads=FKV_HEADS_ALL, copy_stream=None):
+        self._check(self.L.fkv_recall_pending(self._h, layer, heads, _stream(copy_stream)), "fkv_recall_pending")
+
+    def test_lose_selection(self, on):
+        self._check(self.L.fkv_test_lose_selection(self._h, int(on)), "fkv_test_lose_selection")
+
+    def instrument_timestamps(self, on):
+        self._check(self.L.fkv_instrument_timestamps(self._h, int(on)), "fkv_instrument_timestamps")
 
     def sparse_decode_attn(self, layer, q, out, use=FKV_USE_ACTIVE, stream=None):
         self._check(self.L.fkv_sparse_decode_attn(self._h, layer, _ptr(q), _ptr(out), use, _stream(stream)), "fkv_sparse_decode_attn")

@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument checks, arena carving, per-layer state and the
 // stream-ordered schedule of one decode step.  No kernel code here.
 #include "../../include/freekv.h"
+#include "../../include/freekv_instrument.h"
 #include "fkv_internal.h"
 
 #include <cstdio>
@@ -25,6 +26,7 @@ struct LayerState {
   bool have_flags = false;
   bool offload_outstanding = false;
   bool recall_outstanding = false;
+  int recalled = 0;          // placement HOST: which heads' pending pages have been recalled (bit 0 corrected, bit 1 the others)
   int epoch = 0;             // decode steps taken through the one-launch path (selection epochs)
   int last_launches = 0;     // kernel launches of the last fkv_decode_step (compute stream)
   int step_launches = 0;     // launches the last run_step made
@@ -128,6 +130,7 @@ struct fkv_ctx {
   char* host = nullptr;
   std::vector<LayerState> layers;
   std::string err;
+  int device = 0;                     // the HIP device the context was created on
   hipEvent_t ev_fork = nullptr;
   std::vector<int32_t> host_miss;     // FKV_RECALL_MEMCPY: host copies of the miss lists and flags
   std::vector<uint8_t> host_flags;
@@ -165,8 +168,8 @@ struct fkv_ctx {
   float* part_o() const { return reinterpret_cast<float*>(ctx_base() + lay.part_o); }
   float* part_ml() const { return reinterpret_cast<float*>(ctx_base() + lay.part_ml); }
   uint16_t* dbg_page() const { return reinterpret_cast<uint16_t*>(ctx_base() + lay.dbg_page); }
-  bool lose_selection = false;   // FKV_TEST_LOSE_SELECTION=1: corrected heads' attention waits in vain (tests the bounded wait)
-  bool stamp_on = false;   // FKV_TSTAMP=1: kernels record phase timestamps of head 0 (debugging aid)
+  bool lose_selection = false;   // fkv_test_lose_selection: corrected heads' attention waits in vain (tests the bounded wait)
+  bool stamp_on = false;   // fkv_instrument_timestamps: kernels record phase timestamps of head 0 (debugging aid)
   long long* tstamp() const { return stamp_on ? reinterpret_cast<long long*>(ctx_base() + lay.tstamp) : nullptr; }
 
   int fail(int code, const std::string& msg) { err = msg; return code; }
@@ -263,7 +266,8 @@ static int run_plan(fkv_ctx* ctx, int layer, hipStream_t st) {
   LayerState& ls = ctx->layers[layer];
   if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
   launch_plan(ctx->dims, ctx->ids(layer, ls.parity), ctx->ids(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity ^ 1),
-              ctx->slots(layer, ls.parity), ctx->miss(layer), st);
+              ctx->slots(layer, ls.parity), ctx->miss(layer), ls.L / PG, st);
+  ls.recalled = 0;
   return after_launch(ctx, "plan kernel");
 }
 
@@ -295,7 +299,13 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   ctx->cfg = *cfg;
   ctx->lay = l;
   int dev_id = 0, max_lds = 65536;
-  if (hipGetDevice(&dev_id) == hipSuccess) {
+  if (hipGetDevice(&dev_id) != hipSuccess || dev_id < 0 || dev_id >= 64) {
+    g_create_error = "no current HIP device";
+    delete ctx;
+    return FKV_EHIP;
+  }
+  ctx->device = dev_id;
+  {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id) == hipSuccess && v > 0) max_lds = v;
     v = 0;
@@ -306,8 +316,6 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   ctx->dev = static_cast<char*>(dev_arena);
   ctx->host = cfg->placement == FKV_PLACE_HOST ? static_cast<char*>(host_arena) : nullptr;
   ctx->layers.resize(cfg->n_layers);
-  { const char* e = getenv("FKV_TSTAMP"); ctx->stamp_on = e && e[0] == '1'; }
-  { const char* e = getenv("FKV_TEST_LOSE_SELECTION"); ctx->lose_selection = e && e[0] == '1'; }
   hipError_t e = hipMemset(dev_arena, 0, l.total);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
@@ -393,6 +401,7 @@ int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* 
   ls.parity = 0;
   ls.have_prev_q = ls.have_active = ls.have_pending = ls.staged_q = ls.have_flags = false;
   ls.offload_outstanding = ls.recall_outstanding = false;
+  ls.recalled = 0;
   return FKV_OK;
 }
 
@@ -448,14 +457,9 @@ int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* pag
   return FKV_OK;
 }
 
-int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream) {
-  FKV_CHECK_LAYER(ctx, layer);
-  if (heads < 0 || heads > 2) return ctx->fail(FKV_EINVAL, "bad heads selector");
-  if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
+// copy the missing pages of the PENDING selection's chosen heads (by flag or by mask) into their slots
+static int recall_missing(fkv_ctx* ctx, int layer, int heads_mode, const uint8_t* select_by, hipStream_t cs) {
   LayerState& ls = ctx->layers[layer];
-  if (!ls.have_pending) return ctx->fail(FKV_ESTATE, "recall before page_select");
-  if (heads != FKV_HEADS_ALL && !ls.have_flags) return ctx->fail(FKV_ESTATE, "recall by flag before corr_check");
-  hipStream_t cs = static_cast<hipStream_t>(copy_stream);
   if (ls.offload_outstanding) {   // a page offloaded moments ago may be picked already
     FKV_HIP(ctx, hipStreamWaitEvent(cs, ls.ev_offload, 0));
   }
@@ -467,11 +471,12 @@ int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stre
     if (ctx->host_miss.size() < n_int) ctx->host_miss.resize(n_int);
     if (ctx->host_flags.size() < (size_t)n_heads) ctx->host_flags.resize(n_heads);
     FKV_HIP(ctx, hipMemcpyAsync(ctx->host_miss.data(), ctx->miss(layer), n_int * 4, hipMemcpyDeviceToHost, cs));
-    FKV_HIP(ctx, hipMemcpyAsync(ctx->host_flags.data(), ctx->flags(layer), n_heads, hipMemcpyDeviceToHost, cs));
+    if (heads_mode != FKV_HEADS_ALL)
+      FKV_HIP(ctx, hipMemcpyAsync(ctx->host_flags.data(), select_by, n_heads, hipMemcpyDeviceToHost, cs));
     FKV_HIP(ctx, hipStreamSynchronize(cs));
     const PoolDesc pd = ctx->pool_desc(layer);
     for (int h = 0; h < n_heads; ++h) {
-      if (heads != FKV_HEADS_ALL && ((heads == FKV_HEADS_FLAGGED) != (ctx->host_flags[h] != 0))) continue;
+      if (heads_mode != FKV_HEADS_ALL && ((heads_mode == FKV_HEADS_FLAGGED) != (ctx->host_flags[h] != 0))) continue;
       const int32_t* mh = ctx->host_miss.data() + (size_t)h * (1 + 2 * kk);
       for (int i = 0; i < mh[0]; ++i) {
         const uint16_t* src = ctx->host_pool(layer) + ((size_t)h * ctx->lay.max_pages + mh[1 + i]) * UNIT_ELEMS;
@@ -482,8 +487,45 @@ int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stre
     return FKV_OK;
   }
   launch_gather(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ctx->miss(layer), nullptr,
-                ctx->flags(layer), heads, cs);
+                select_by, heads_mode, cs);
   return after_launch(ctx, "gather kernel");
+}
+
+int fkv_recall_pending(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (heads < 0 || heads > 2) return ctx->fail(FKV_EINVAL, "bad heads selector");
+  if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
+  LayerState& ls = ctx->layers[layer];
+  if (!ls.have_pending) return ctx->fail(FKV_ESTATE, "recall before page_select");
+  if (heads != FKV_HEADS_ALL && !ls.have_flags) return ctx->fail(FKV_ESTATE, "recall by flag before corr_check");
+  int rc = recall_missing(ctx, layer, heads, ctx->flags(layer), static_cast<hipStream_t>(copy_stream));
+  if (rc) return rc;
+  ls.recalled |= heads == FKV_HEADS_ALL ? 3 : heads == FKV_HEADS_FLAGGED ? 1 : 2;
+  return FKV_OK;
+}
+
+int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, const int32_t* page_ids_dev, const uint8_t* head_mask_dev, void* copy_stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
+  LayerState& ls = ctx->layers[layer];
+  hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+  if (page_ids_dev) {
+    // the caller's list becomes the PENDING selection: planned against ACTIVE's slots like one of the library's own
+    if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
+    int rc = wait_recall(ctx, ls, cs);
+    if (rc) return rc;
+    const size_t n = (size_t)ctx->cfg.batch * ctx->cfg.n_kv_heads * ctx->lay.k * sizeof(int32_t);
+    if (n) FKV_HIP(ctx, hipMemcpyAsync(ctx->ids(layer, ls.parity), page_ids_dev, n, hipMemcpyDeviceToDevice, cs));
+    rc = run_plan(ctx, layer, cs);
+    if (rc) return rc;
+    ls.have_pending = true;
+  } else if (!ls.have_pending) {
+    return ctx->fail(FKV_ESTATE, "recall of the pending selection before page_select");
+  }
+  int rc = recall_missing(ctx, layer, head_mask_dev ? FKV_HEADS_FLAGGED : FKV_HEADS_ALL, head_mask_dev, cs);
+  if (rc) return rc;
+  if (!head_mask_dev) ls.recalled = 3;
+  return FKV_OK;
 }
 
 int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev, int32_t use, void* stream) {
@@ -536,6 +578,8 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer) {
   FKV_CHECK_LAYER(ctx, layer);
   LayerState& ls = ctx->layers[layer];
   if (!ls.have_pending || !ls.staged_q) return ctx->fail(FKV_ESTATE, "commit needs corr_check and page_select first");
+  if (ctx->cfg.placement == FKV_PLACE_HOST && ctx->lay.k > 0 && ls.recalled != 3)
+    return ctx->fail(FKV_ESTATE, "commit before every head's picked pages were recalled: the page cache would hold unfilled slots");
   ls.parity ^= 1;
   ls.have_prev_q = true;
   ls.have_active = true;
@@ -601,7 +645,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   bool deferred = false;
   if (host_pool) {
     // corrected heads: recall before this step's attention (Sec. 3.3)
-    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_FLAGGED, compute_stream);
+    rc = fkv_recall_pending(ctx, layer, FKV_HEADS_FLAGGED, compute_stream);
     if (rc) return rc;
     // other heads: recall for the next step on the copy stream, off the critical path
     // (Sec. 3.2).  It writes only slots that this step's attention does not read, so it may run
@@ -610,7 +654,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     if (cs != st) {
       FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
       FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
-      rc = fkv_recall_pages(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
+      rc = fkv_recall_pending(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
       if (rc) return rc;
       FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
       deferred = true;     // the next step of this layer waits for it, not this step's attention
@@ -619,13 +663,25 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   rc = fkv_sparse_decode_attn(ctx, layer, q_dev, out_dev, FKV_USE_BY_FLAG, compute_stream);
   if (rc) return rc;
   if (host_pool && cs == st) {
-    rc = fkv_recall_pages(ctx, layer, FKV_HEADS_UNFLAGGED, compute_stream);
+    rc = fkv_recall_pending(ctx, layer, FKV_HEADS_UNFLAGGED, compute_stream);
     if (rc) return rc;
   }
   ls.recall_outstanding = deferred;
   // step roles (1-3) + attention, and with the host pool the plan and the corrected heads' gather
   ls.last_launches = ls.step_launches + 1 + (host_pool ? 2 : 0);
   return fkv_commit(ctx, layer);
+}
+
+int fkv_test_lose_selection(fkv_ctx* ctx, int32_t on) {
+  if (!ctx) return FKV_EINVAL;
+  ctx->lose_selection = on != 0;
+  return FKV_OK;
+}
+
+int fkv_instrument_timestamps(fkv_ctx* ctx, int32_t on) {
+  if (!ctx) return FKV_EINVAL;
+  ctx->stamp_on = on != 0;
+  return FKV_OK;
 }
 
 int fkv_profile_enable(fkv_ctx* ctx, int32_t max_launches) {
@@ -775,15 +831,16 @@ int fkv_debug_read_page(fkv_ctx* ctx, int32_t layer, int32_t request, int32_t kv
   } else if (where == 1) {
     if (c.placement != FKV_PLACE_HOST) return ctx->fail(FKV_ESTATE, "no host pool in HBM placement");
     unit = ctx->host_pool(layer) + (head * ctx->lay.max_pages + page) * UNIT_ELEMS;
-  } else if (where == 2) {
+  } else if (where == 2 || where == 3) {
     if (c.placement != FKV_PLACE_HOST) return ctx->fail(FKV_ESTATE, "no page cache in HBM placement");
     const size_t kk = ctx->lay.k;
+    const int half = where == 2 ? ls.parity ^ 1 : ls.parity;
     std::vector<int32_t> idv(kk), slv(kk);
-    FKV_HIP(ctx, hipMemcpy(idv.data(), ctx->ids(layer, ls.parity ^ 1) + head * kk, kk * 4, hipMemcpyDeviceToHost));
-    FKV_HIP(ctx, hipMemcpy(slv.data(), ctx->slots(layer, ls.parity ^ 1) + head * kk, kk * 4, hipMemcpyDeviceToHost));
+    FKV_HIP(ctx, hipMemcpy(idv.data(), ctx->ids(layer, half) + head * kk, kk * 4, hipMemcpyDeviceToHost));
+    FKV_HIP(ctx, hipMemcpy(slv.data(), ctx->slots(layer, half) + head * kk, kk * 4, hipMemcpyDeviceToHost));
     int slot = -1;
     for (size_t i = 0; i < kk; ++i) if (idv[i] == page) slot = slv[i];
-    if (slot < 0) return ctx->fail(FKV_ERANGE, "page is not in the active selection");
+    if (slot < 0) return ctx->fail(FKV_ERANGE, "page is not in that selection");
     unit = pd.pool + (head * pd.units_per_head + pd.sel_base + slot) * UNIT_ELEMS;
   } else {
     return ctx->fail(FKV_EINVAL, "bad where");

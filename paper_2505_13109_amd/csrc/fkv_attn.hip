@@ -1,6 +1,5 @@
 // Stand-alone launch of sparse decode attention (device code in fkv_attn_dev.h).
 #include "fkv_attn_dev.h"
-#include <cstdlib>
 
 namespace fkv {
 
@@ -11,8 +10,8 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(AttnArgs a) {
   attn_block<DT, NW>(a, blockIdx.x, blockIdx.y, blockIdx.z, lds);
 }
 
-// tuning knob for experiments: pages per block (0 = choose from the shape)
-static int g_pps_override = [] { const char* e = getenv("FKV_ATTN_PPS"); return e ? atoi(e) : 0; }();
+// experiment builds only (see knob()): pages per block (0 = choose from the shape)
+static const int g_pps_override = knob("FKV_ATTN_PPS", 0);
 
 // pages per block of NW waves for a head with n_att attended pages
 int attn_pages_per_block(int n_att, int heads, int max_splits, int nw) {

@@ -174,20 +174,6 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
     } else {
       pending = true;
     }
-    if (pending) {
-      // a corrected head attends with this step's selection: wait for the block that makes it.
-      // That block belongs to the scoring blocks of this launch, which all have lower block
-      // indices than any attention block and never wait for anything, so they are running or
-      // done; the wait is bounded all the same.
-      if (threadIdx.x == 0) {
-        int it = 0;
-        while (__hip_atomic_load(a.sel_done + head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
-          if (++it > (1 << 16)) { *a.status = 1; break; }   // ~0.1 s
-          __builtin_amdgcn_s_sleep(4);
-        }
-      }
-      __syncthreads();
-    }
   } else {
     pending = a.use == 1 || (a.use == 2 && a.flags[head] != 0);
   }
@@ -208,15 +194,49 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
 #pragma unroll
   for (int cb = 0; cb < 8; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
-  // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
+  // A corrected head of a fused launch attends with this step's selection, which other blocks of
+  // the same launch are still making.  Only the k picked positions of the attend list depend on it:
+  // the wave first attends its sink, window and open-page positions (phase 0), then waits for the
+  // selection and attends its picked positions (phase 1).  Everything else runs as one phase.
+  const bool two_phase = a.fused && pending && k > 0;
+  const int pk_lo = g.n_sink, pk_hi = g.n_sink + k;
   const int p_end = min(n_att, (split + 1) * a.pps);
-  int pos = pos0, unit = -1, n_valid = PG, page = -1;
-  if (pos < p_end) unit = attend_unit(al, pd, pos, n_valid, page, spec && !pending, spec_id);
-  if (unit < 0) {
-    pos += NW;
-    while (pos < p_end && (unit = attend_unit(al, pd, pos, n_valid, page)) < 0) pos += NW;
-  }
+  bool timed_out = false;
+  for (int phase = 0; phase < (two_phase ? 2 : 1); ++phase) {
+    // first position of this wave, from `from` on, that belongs to the phase and holds a page
+    int n_valid = PG, page = -1;
+    auto find = [&](int from, int& nv, int& pg) -> int2 {
+      for (int p2 = from; p2 < p_end; p2 += NW) {
+        if (two_phase && ((p2 >= pk_lo && p2 < pk_hi) != (phase == 1))) continue;
+        const int u = attend_unit(al, pd, p2, nv, pg, spec && !pending && p2 == pos0, spec_id);
+        if (u >= 0) return make_int2(p2, u);
+      }
+      return make_int2(p_end, -1);
+    };
+    if (phase == 1) {
+      // does this wave have a picked position at all?
+      bool mine = false;
+      for (int p2 = pos0; p2 < p_end; p2 += NW) mine = mine || (p2 >= pk_lo && p2 < pk_hi);
+      if (!mine) break;
+      // Wait for the block that makes this head's selection.  It is one of the scoring blocks of
+      // this launch, which all have lower block indices than any attention block and never wait
+      // for anything, so it is running or done; the wait is bounded all the same.  The whole wave
+      // polls the same word (one request per poll).
+      int it = 0;
+      while (__hip_atomic_load(a.sel_done + head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
+        if (++it > (1 << 16)) { timed_out = true; break; }   // ~0.1 s
+        __builtin_amdgcn_s_sleep(4);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the id loads below stay behind the poll
+      if (timed_out) {
+        if (lane == 0) *a.status = 1;
+        break;                                                 // the ids are not there: read nothing
+      }
+    }
+    // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
+    // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
+    int2 cur = find(pos0, n_valid, page);
+    int pos = cur.x, unit = cur.y;
   uint4 kw[8], vw[8];
   if (unit >= 0) {
     const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)unit * UNIT_ELEMS) + lane;
@@ -227,8 +247,9 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   }
   while (unit >= 0) {
     // next page of this wave, if any
-    int npos = pos + NW, nunit = -1, nn_valid = PG, npage = -1;
-    while (npos < p_end && (nunit = attend_unit(al, pd, npos, nn_valid, npage)) < 0) npos += NW;
+    int nn_valid = PG, npage = -1;
+    const int2 nxt = find(pos + NW, nn_valid, npage);
+    const int npos = nxt.x, nunit = nxt.y;
     uint4 kn[8], vn[8];
     if (nunit >= 0) {
       const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)nunit * UNIT_ELEMS) + lane;
@@ -309,6 +330,11 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
       for (int j = 0; j < 8; ++j) { kw[j] = kn[j]; vw[j] = vn[j]; }
     }
   }
+  }   // phases
+  // A wave whose wait ran out has not read its picked pages: make that visible on the data path.
+  // NaN in its sum poisons the block's partial and, through the merge, every output row of the
+  // KV head's query group.
+  if (timed_out) l_run = __builtin_nanf("");
   if (split == 0) FKV_ASTAMP(17);
   // per-wave totals of l over the 4 row blocks
   l_run += __shfl_xor(l_run, 16, 64);

@@ -161,11 +161,13 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, con
 // A page hits iff it is in the ACTIVE selection (it keeps that slot).  Misses go, in
 // ascending page order, to the lowest-numbered slots the ACTIVE selection does not use.
 // grid (n_kv, batch), 64 threads (one wave); pool of 2k slots per head; k <= 1024.
-__global__ __launch_bounds__(64) void plan_kernel(const int32_t* __restrict__ new_ids,
+// An id that is not a full page of the context (a caller's list may hold anything) is dropped:
+// rewritten to -1 in new_ids, so that neither the gather nor attention ever forms its address.
+__global__ __launch_bounds__(64) void plan_kernel(int32_t* __restrict__ new_ids,
                                                   const int32_t* __restrict__ act_ids,
                                                   const int32_t* __restrict__ act_slots,
                                                   int32_t* __restrict__ new_slots,
-                                                  int32_t* __restrict__ miss, int k, int n_kv) {
+                                                  int32_t* __restrict__ miss, int k, int n_kv, int n_full) {
   extern __shared__ int32_t sm[];          // used[2k], aid[k], aslot[k], nid[k], nslot[k], freelist[2k]
   int32_t* used = sm;
   int32_t* aid = sm + 2 * k;
@@ -181,7 +183,9 @@ __global__ __launch_bounds__(64) void plan_kernel(const int32_t* __restrict__ ne
   for (int i = lane; i < k; i += 64) {     // all lists in one round trip
     aid[i] = act_ids[hb + i];
     aslot[i] = act_slots[hb + i];
-    nid[i] = new_ids[hb + i];
+    const int32_t id = new_ids[hb + i];
+    nid[i] = id < n_full ? id : -1;
+    if (id >= n_full) new_ids[hb + i] = -1;
   }
   __syncthreads();
   for (int i = lane; i < k; i += 64) {
@@ -267,11 +271,11 @@ void launch_offload(const Dims& d, const PoolDesc& pd, uint16_t* host_pool, int 
   offload_kernel<<<grid, 256, 0, st>>>(pd, host_pool, page, d.n_kv, d.max_pages);
 }
 
-void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
-                 int32_t* new_slots, int32_t* miss, hipStream_t st) {
+void launch_plan(const Dims& d, int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
+                 int32_t* new_slots, int32_t* miss, int n_full, hipStream_t st) {
   if (d.k == 0) return;
   dim3 grid(d.n_kv, d.batch);
-  plan_kernel<<<grid, 64, 8 * d.k * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv);
+  plan_kernel<<<grid, 64, 8 * d.k * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv, n_full);
 }
 
 void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,

@@ -136,21 +136,43 @@ __device__ __forceinline__ float2 ld_dev2(const float* p) {
   return make_float2(__uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
 }
 
+// All vector-memory operations this wave has issued so far -- loads and stores count on the same
+// counter on this target -- have completed.  For a store issued at device scope (st_dev*: written
+// through to the device coherence point) "completed" means it is visible to every compute unit of
+// the GPU, which is what the release side of the exchange below needs; no L2 write-back is involved
+// because nothing that is exchanged was written with a plain store.
+__device__ __forceinline__ void wait_vector_memory() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// Release side of an exchange: every wave of the block waits for its own device-scope stores, the
+// barrier then makes "all of the block's stores are visible" a fact thread 0 may publish.  The
+// workgroup-scope fences only pin the compiler's ordering around the barrier.
+__device__ __forceinline__ void block_release() {
+  wait_vector_memory();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+}
+// Acquire side: after thread 0 has observed the other blocks' publication, the barrier hands that
+// knowledge to the block and the fence keeps every later (device-scope, ld_dev*) load behind it.
+__device__ __forceinline__ void block_acquire() {
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // Block-wide "am I the last one?" for a group of `expected` blocks sharing `counter`.
-// What the block stored with st_dev* before the call has completed when the counter is
-// bumped, so the block that gets `true` can read every other block's values with ld_dev*.
-// Resets the counter for the next launch.
+// What the block stored with st_dev* before the call is visible device-wide when the counter is
+// bumped (block_release), so the block that gets `true` can read every other block's values with
+// ld_dev*.  Resets the counter for the next launch.
 __device__ __forceinline__ bool last_block_done(int* counter, int expected) {
   __shared__ int s_last;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores have been acknowledged
-  __syncthreads();
+  block_release();
   if (threadIdx.x == 0) {
     const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == expected - 1);
     if (s_last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  __syncthreads();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  block_acquire();
   return s_last != 0;
 }
 

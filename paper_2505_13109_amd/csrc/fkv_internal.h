@@ -2,8 +2,21 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 namespace fkv {
+
+// Dispatch overrides for experiments (sweeps of tile and launch shapes).  They are read from the
+// environment only in a build with -DFKV_EXPERIMENT_KNOBS; the product library has none.
+inline int knob(const char* name, int dflt) {
+#ifdef FKV_EXPERIMENT_KNOBS
+  const char* e = getenv(name);
+  return e ? atoi(e) : dflt;
+#else
+  (void)name;
+  return dflt;
+#endif
+}
 
 constexpr int D = 128;            // head_dim
 constexpr int PG = 32;            // page size p
@@ -80,8 +93,9 @@ void launch_load_prefix(const Dims& d, const PoolDesc& pd, uint16_t* summ, uint1
 void launch_summary_recompute(const Dims& d, const PoolDesc& pd, uint16_t* summ, int first_page,
                               int n_pages, Geom g, hipStream_t st);
 void launch_offload(const Dims& d, const PoolDesc& pd, uint16_t* host_pool, int page, hipStream_t st);
-void launch_plan(const Dims& d, const int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
-                 int32_t* new_slots, int32_t* miss, hipStream_t st);
+// new_ids is read and, where an id is not a full page (id < 0 or id >= n_full), rewritten to -1
+void launch_plan(const Dims& d, int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
+                 int32_t* new_slots, int32_t* miss, int n_full, hipStream_t st);
 void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
                    const int32_t* new_slots_unused, const uint8_t* flags, int heads, hipStream_t st);
 // returns the number of splits written per KV head

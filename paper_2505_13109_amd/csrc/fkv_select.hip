@@ -4,7 +4,6 @@
 // The roles themselves are in fkv_step_dev.h, attention in fkv_attn_dev.h.
 #include "fkv_step_dev.h"
 #include "fkv_attn_dev.h"
-#include <cstdlib>
 
 #pragma clang fp contract(off)
 
@@ -43,10 +42,11 @@ constexpr size_t kLdsPerUnit = 150 * 1024;   // of the 160 KiB of a compute unit
 constexpr int kComputeUnits = 256;
 constexpr int kFuseMaxBlocks = kComputeUnits;       // launches up to this size run the selection in their last scoring blocks
 constexpr int kLayerMaxBlocks = 4 * kComputeUnits;  // shapes up to this size take the one-launch layer kernel
-static int g_chunks_per_block = [] { const char* e = getenv("FKV_SCORE_CHUNKS"); return e ? atoi(e) : 0; }();   // experiments
-static int g_fuse_mode = [] { const char* e = getenv("FKV_FUSE_SELECT"); return e ? atoi(e) : -1; }();   // experiments: 0 never, 1 always
-// tuning knob for experiments: passes a scoring block makes (default: chosen from the shape)
-static int g_min_passes = [] { const char* e = getenv("FKV_LAYER_PASSES"); return e ? atoi(e) : 0; }();
+// experiment builds only (see knob()): chunks per scoring block, selection inside the scoring launch
+// (0 never, 1 always), passes a scoring block makes; the defaults choose from the shape
+static const int g_chunks_per_block = knob("FKV_SCORE_CHUNKS", 0);
+static const int g_fuse_mode = knob("FKV_FUSE_SELECT", -1);
+static const int g_min_passes = knob("FKV_LAYER_PASSES", 0);
 // may every block of a `grid`-block launch carry `lds` bytes without starving the scoring blocks?
 static bool lds_fits_launch(size_t lds, int grid) {
   int per_unit = (grid + kComputeUnits - 1) / kComputeUnits;   // blocks a unit should hold at once
@@ -183,8 +183,9 @@ __global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
   attn_block<DT, STEP_WAVES>(a.at, split, head % a.s.n_kv, head / a.s.n_kv, reinterpret_cast<float*>(dyn_lds));
 }
 
-static bool g_no_layer_kernel = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '1'; }();
-static bool g_layer_always = [] { const char* e = getenv("FKV_NO_LAYER_KERNEL"); return e && e[0] == '0'; }();   // experiments
+// experiment builds only: 1 = always separate launches, 0 = one launch whenever it fits
+static const bool g_no_layer_kernel = knob("FKV_NO_LAYER_KERNEL", -1) == 1;
+static const bool g_layer_always = knob("FKV_NO_LAYER_KERNEL", -1) == 0;
 
 template <int DT, int G>
 static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {

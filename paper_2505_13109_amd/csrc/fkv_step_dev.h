@@ -719,9 +719,8 @@ __device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t*
   if (a.tstamp && threadIdx.x == 0) a.tstamp[24 + (head & 7)] = wall_clock64();
 #endif
   if (a.sel_done) {
-    // the ids went out with device-scope stores; once they are acknowledged, announce them
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
+    // the ids went out with device-scope stores; once every wave's have completed, announce them
+    block_release();
     if (threadIdx.x == 0) __hip_atomic_store(a.sel_done + head, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   // the pooled scores, kept for inspection; after the announcement, which nothing here should delay

@@ -119,43 +119,51 @@ class Pair:
         res = []
         for r in range(wl.batch):
             res.append(self.oracles[(li, r)].step(self.q[(li, r)][0][t], self.kd[(li, r)][0][t], self.vd[(li, r)][0][t]))
-        if not check:
-            return res
-        ids = self.g.debug_read(li, B.DBG_ACTIVE_IDS)        # after commit the step's selection is ACTIVE
-        flags = self.g.debug_read(li, B.DBG_FLAGS)
-        out = self.out.cpu().numpy()
+        if check:
+            self.compare(li, t, res, self.read_step(li, deep), deep)
+        return res
+
+    def read_step(self, li, deep):
+        """What the HIP side holds after decode step of layer index li (blocking reads)."""
+        got = dict(ids=self.g.debug_read(li, B.DBG_ACTIVE_IDS),      # after commit the step's selection is ACTIVE
+                   flags=self.g.debug_read(li, B.DBG_FLAGS), out=self.out.cpu().numpy())
         if deep:
-            Pw = self.g.debug_read(li, B.DBG_WEIGHTS)
-            Sc = self.g.debug_read(li, B.DBG_SCORES)
-            cosv = self.g.debug_read(li, B.DBG_COSINE)
+            got.update(P=self.g.debug_read(li, B.DBG_WEIGHTS), score=self.g.debug_read(li, B.DBG_SCORES),
+                       cosine=self.g.debug_read(li, B.DBG_COSINE))
         if self.placement == 1:
-            miss = self.g.debug_read(li, B.DBG_MISS)
+            got["miss"] = self.g.debug_read(li, B.DBG_MISS)
+        return got
+
+    def compare(self, li, t, res, got, deep):
+        """HIP results `got` of one layer-step against the oracle's `res` (one per request)."""
+        wl = self.wl
         for r in range(wl.batch):
             ref = res[r]
             gm = ref["geom"]
+            if isinstance(gm, tuple):
+                gm = O.Geometry(*gm)
             tag = f"layer {self.layers[li]} step {t} request {r} L {gm.L}"
-            if deep and wl.k_pages > 0:      # with nothing selectable the library skips scoring altogether
+            if deep and wl.k_pages > 0 and "P" in ref:      # with nothing selectable the library skips scoring altogether
                 lo, hi = gm.cand_lo, gm.cand_lo + gm.n_cand
                 # a pooled query has one row of weights per KV head, kept in the row of the group's first head
-                Pg = Pw[r, ::wl.n_q_heads // wl.n_kv_heads, lo:hi] if self.q_pooled else Pw[r, :, lo:hi]
+                Pg = got["P"][r, ::wl.n_q_heads // wl.n_kv_heads, lo:hi] if self.q_pooled else got["P"][r, :, lo:hi]
                 assert np.array_equal(Pg, ref["P"]), f"page weights differ: {tag}: {_diff(Pg, ref['P'])}"
-                assert np.array_equal(Sc[r, :, lo:hi], ref["score"]), f"pooled scores differ: {tag}: {_diff(Sc[r, :, lo:hi], ref['score'])}"
+                assert np.array_equal(got["score"][r, :, lo:hi], ref["score"]), f"pooled scores differ: {tag}: {_diff(got['score'][r, :, lo:hi], ref['score'])}"
                 if t > 0:
-                    np.testing.assert_allclose(cosv[r], ref["cosine"], rtol=0, atol=1e-12, err_msg=tag)
-            assert np.array_equal(flags[r], ref["flags"]), f"flags differ: {tag}: {flags[r]} vs {ref['flags']}"
-            assert np.array_equal(ids[r], ref["new_ids"]), f"page ids differ: {tag}"
-            err = rel_err_per_head(out[r], ref["out"])
+                    np.testing.assert_allclose(got["cosine"][r], ref["cosine"], rtol=0, atol=1e-12, err_msg=tag)
+            assert np.array_equal(got["flags"][r], ref["flags"]), f"flags differ: {tag}: {got['flags'][r]} vs {ref['flags']}"
+            assert np.array_equal(got["ids"][r], ref["new_ids"]), f"page ids differ: {tag}"
+            err = rel_err_per_head(got["out"][r], ref["out"])
             assert err.max() <= TOL_OUT, f"attention output off by {err.max():.3e}: {tag}"
             self.stats["max_rel"] = max(self.stats["max_rel"], float(err.max()))
             self.stats["flagged"] += int(ref["flags"].sum())
             self.stats["heads"] += wl.n_kv_heads
             if self.placement == 1:
                 for m in range(wl.n_kv_heads):
-                    n = int(miss[r, m, 0])
-                    assert sorted(miss[r, m, 1:1 + n].tolist()) == ref["miss"][m], f"miss list differs: {tag} head {m}"
+                    n = int(got["miss"][r, m, 0])
+                    assert sorted(got["miss"][r, m, 1:1 + n].tolist()) == ref["miss"][m], f"miss list differs: {tag} head {m}"
                     self.stats["misses"] += n
                     self.stats["picked"] += int((ref["new_ids"][m] >= 0).sum())
-        return res
 
     def check_nhd_export(self, li):
         """The NHD-layout pool of the ACTIVE selection equals the oracle's, byte for byte."""
@@ -186,3 +194,77 @@ class Pair:
         for li in range(len(self.layers)):
             self.g.health(li)            # no kernel gave up a bounded wait
         self.g.close()
+
+
+class PoolPair(Pair):
+    """Pair whose oracles live in worker processes (tests/oracle_pool.py): for the cases whose oracle
+    state or oracle time is too big for one process.  Every (layer, request) unit generates its own
+    inputs in its worker; the parent uploads the context bits the worker sends back and draws only the
+    small per-step streams itself."""
+
+    def __init__(self, wl, layers, pool, ctx=None, placement=None, tau=None, steps=None, keep_prefix=False):
+        self.wl = wl
+        self.layers = list(layers)
+        self.pool = pool
+        self.n_ctx = wl.ctx if ctx is None else ctx
+        self.steps = wl.steps if steps is None else steps
+        self.placement = wl.placement if placement is None else placement
+        self.tau = wl.tau if tau is None else tau
+        p = wl.page_size
+        self.max_ctx = ((self.n_ctx + self.steps + p - 1) // p) * p
+        self.q_pooled = False
+        self.g = fkv.FreeKV(n_layers=len(self.layers), batch=wl.batch, n_q_heads=wl.n_q_heads,
+                            n_kv_heads=wl.n_kv_heads, max_ctx=self.max_ctx, budget=wl.budget,
+                            sink=wl.sink, window=wl.window, tau=self.tau, dtype=wl.dtype, placement=self.placement)
+        self.copy_stream = torch.cuda.Stream()
+        self.oracles = {}
+        self.q, self.kd, self.vd = {}, {}, {}
+        n_workers = len(pool.conns)
+        units = [(li, r) for li in range(len(self.layers)) for r in range(wl.batch)]
+        for i, (li, r) in enumerate(units):
+            pool.load_async((id(self), li, r), i % n_workers, wl=wl, layer=self.layers[li], request=r, n_ctx=self.n_ctx,
+                            steps=self.steps, tau=self.tau, max_ctx=self.max_ctx, select_pooling="MeanS",
+                            corr_pooling="mean", want_bits=True, keep_prefix=keep_prefix)
+        for li, layer in enumerate(self.layers):
+            Kd = torch.empty((wl.batch, self.n_ctx, wl.n_kv_heads, wl.head_dim), dtype=torch.int16, device="cuda")
+            Vd = torch.empty_like(Kd)
+            for r in range(wl.batch):
+                Kb, Vb = pool.load_result((id(self), li, r), True)
+                Kd[r].copy_(torch.from_numpy(Kb.view(np.int16)))
+                Vd[r].copy_(torch.from_numpy(Vb.view(np.int16)))
+                del Kb, Vb
+                self.q[(li, r)] = W.query_stream(wl, layer, r, self.steps)
+                self.kd[(li, r)], self.vd[(li, r)] = W.kv_decode_tokens(wl, layer, r, self.steps)
+            dt = torch.float16 if wl.dtype == "fp16" else torch.bfloat16
+            self.g.load_prefix(li, Kd.view(dt), Vd.view(dt))
+            torch.cuda.synchronize()
+            del Kd, Vd
+        self.out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda")
+        self.stats = dict(max_rel=0.0, flagged=0, heads=0, misses=0, picked=0)
+
+    def key(self, li, r):
+        return (id(self), li, r)
+
+    def step_all_layers(self, t, deep=True):
+        """Decode step t of every layer: the oracles work in their processes while the HIP side decodes."""
+        wl = self.wl
+        for li in range(len(self.layers)):
+            for r in range(wl.batch):
+                self.pool.steps_async(self.key(li, r), t, t + 1, 1 if deep else 0)
+        got = []
+        for li in range(len(self.layers)):
+            q, k, v = self.step_inputs(li, t)
+            self.g.decode_step(li, q, k, v, self.out, copy_stream=self.copy_stream)
+            got.append(self.read_step(li, deep))
+        for li in range(len(self.layers)):
+            res = [self.pool.result(self.key(li, r))[0] for r in range(wl.batch)]
+            self.compare(li, t, res, got[li], deep)
+
+    def check_summaries(self, li):
+        wl = self.wl
+        s = W.decode(self.g.debug_read(li, B.DBG_SUMMARIES), wl.dtype)
+        for r in range(wl.batch):
+            kmax, kmin = self.pool.summaries(self.key(li, r))
+            n_page = kmax.shape[0]
+            assert np.array_equal(s[r, :, 0, :n_page, :], kmax.transpose(1, 0, 2)), "kmax"
+            assert np.array_equal(s[r, :, 1, :n_page, :], kmin.transpose(1, 0, 2)), "kmin"
