@@ -201,6 +201,20 @@ int fkv_recall_pending(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_st
 int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev,
                            int32_t use, void* stream);
 
+/* fkv_sparse_decode_attn for callers that cannot allocate device memory or hand over a workspace
+ * sized for it: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and the same result, but the split partials, their (max, sum) pairs and
+ * the last-block counters live in a static device array of FKV_STATIC_SCRATCH_BYTES that the library
+ * itself holds on every GPU it runs on (until the process ends), not in the caller's arena.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine) and clears what must
+ * start at zero with a small kernel, so it may be captured.  A shape whose partials do not fit
+ * (heads x splits x G x (d + 2) x 4 bytes, splits as chosen for the shape) is refused with FKV_ENOMEM
+ * and a message that names both sizes.  Every call on one GPU shares that GPU's array: calls that
+ * overlap in time on one GPU (different streams, different contexts) race; serialise them. */
+#define FKV_STATIC_SCRATCH_BYTES (2u << 20)
+int fkv_sparse_decode_attn_static(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev,
+                                  int32_t use, void* stream);
+
 /* The hybrid layouts taken literally (Sec. 4.2, "Hybrid layouts" / "Streamed recall"): convert the pages
  * that sparse attention would read with selector `use` (FKV_USE_*) into an NHD-layout pool for a
  * kernel that wants tokens with all KV heads side by side.

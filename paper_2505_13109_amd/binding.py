@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
     "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
-    "fkv_recall_pending", "fkv_test_lose_selection", "fkv_instrument_timestamps",
+    "fkv_sparse_decode_attn_static", "fkv_recall_pending", "fkv_test_lose_selection", "fkv_instrument_timestamps",
 )
 
 
@@ -83,6 +83,7 @@ def lib() -> C.CDLL:
         "fkv_test_lose_selection": (C.c_int, [vp, i32]),
         "fkv_instrument_timestamps": (C.c_int, [vp, i32]),
         "fkv_sparse_decode_attn": (C.c_int, [vp, i32, vp, vp, i32, vp]),
+        "fkv_sparse_decode_attn_static": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_commit": (C.c_int, [vp, i32]),
         "fkv_decode_step": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
         "fkv_export_nhd": (C.c_int, [vp, i32, i32, vp, vp, i32, vp]),
@@ -202,6 +203,10 @@ class FreeKV:
 
     def sparse_decode_attn(self, layer, q, out, use=FKV_USE_ACTIVE, stream=None):
         self._check(self.L.fkv_sparse_decode_attn(self._h, layer, _ptr(q), _ptr(out), use, _stream(stream)), "fkv_sparse_decode_attn")
+
+    def sparse_decode_attn_static(self, layer, q, out, use=FKV_USE_ACTIVE, stream=None):
+        self._check(self.L.fkv_sparse_decode_attn_static(self._h, layer, _ptr(q), _ptr(out), use, _stream(stream)),
+                    "fkv_sparse_decode_attn_static")
 
     def export_nhd(self, layer, nhd_pool, slot_pages, use=FKV_USE_ACTIVE, stream=None):
         """nhd_pool [batch, n_slots, 2, page, n_kv, d] storage type, slot_pages [batch, n_kv, n_slots] int32."""

@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument checks, arena carving, per-layer state and the
-// stream-ordered schedule of one decode step.  No kernel code here.
+// stream-ordered schedule of one decode step.  No kernel code here; the one device-side object
+// is the library-owned scratch array of the entry point that must not allocate.
 #include "../../include/freekv.h"
 #include "../../include/freekv_instrument.h"
 #include "fkv_internal.h"
@@ -15,6 +16,14 @@ using namespace fkv;
 namespace {
 
 std::string g_create_error;
+
+// Scratch of fkv_sparse_decode_attn_static (split partials, their (m, l) pairs, last-block counters):
+// one copy per GPU, held until the process ends.  In host code the array's name is only a handle;
+// its device address is looked up once per device (fkv_create) and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = FKV_STATIC_SCRATCH_BYTES;   // 2 MiB
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
 
 struct LayerState {
   int L = 0;                 // tokens cached
@@ -299,12 +308,22 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   ctx->cfg = *cfg;
   ctx->lay = l;
   int dev_id = 0, max_lds = 65536;
-  if (hipGetDevice(&dev_id) != hipSuccess || dev_id < 0 || dev_id >= 64) {
+  if (hipGetDevice(&dev_id) != hipSuccess || dev_id < 0 || dev_id >= kMaxDevices) {
     g_create_error = "no current HIP device";
     delete ctx;
     return FKV_EHIP;
   }
   ctx->device = dev_id;
+  if (!g_scratch_ptr[dev_id]) {     // this device's copy of the static scratch array
+    void* ptr = nullptr;
+    const hipError_t es = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (es != hipSuccess || !ptr) {
+      g_create_error = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(es);
+      delete ctx;
+      return FKV_EHIP;
+    }
+    g_scratch_ptr[dev_id] = ptr;
+  }
   {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id) == hipSuccess && v > 0) max_lds = v;
@@ -550,6 +569,45 @@ int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float
               ctx->flags(layer), use, ctx->part_o(), ctx->part_ml(), ctx->lay.max_splits, ctx->attn_counters(layer),
               out_dev, g, st, e0, e1, ctx->tstamp());
   return after_launch(ctx, "attention kernels");
+}
+
+int fkv_sparse_decode_attn_static(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev, int32_t use, void* stream) {
+  FKV_CHECK_LAYER(ctx, layer);
+  if (!q_dev || !out_dev) return ctx->fail(FKV_EINVAL, "null q or out");
+  if (use < 0 || use > 2) return ctx->fail(FKV_EINVAL, "bad use selector");
+  LayerState& ls = ctx->layers[layer];
+  if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
+  if (use != FKV_USE_ACTIVE && !ls.have_pending) return ctx->fail(FKV_ESTATE, "attention on the pending selection before page_select");
+  if (use == FKV_USE_BY_FLAG && !ls.have_flags) return ctx->fail(FKV_ESTATE, "attention by flag before corr_check");
+  char* base = static_cast<char*>(g_scratch_ptr[ctx->device]);
+  if (!base) return ctx->fail(FKV_ESTATE, "no static scratch on this device");
+  // the split this shape takes, and what its partials need (stride = the splits actually written)
+  const fkv_config& c = ctx->cfg;
+  const Geom g = make_geom(c, ls.L);
+  const int heads = c.batch * c.n_kv_heads, G = c.n_q_heads / c.n_kv_heads;
+  const int n_att = g.n_sink + ctx->lay.k + g.n_win + (g.r > 0 ? 1 : 0);
+  const int pps = attn_pages_per_block(n_att, heads, ctx->lay.max_splits, 4);
+  const int n_splits = (n_att + pps - 1) / pps;
+  const size_t b_cnt = align_up((size_t)heads * sizeof(int));
+  const size_t b_ml = align_up((size_t)heads * n_splits * G * 2 * sizeof(float));
+  const size_t b_o = align_up((size_t)heads * n_splits * G * D * sizeof(float));
+  if (b_cnt + b_ml + b_o > kStaticScratchBytes) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "static scratch too small: this shape needs %zu bytes, the library holds %zu", b_cnt + b_ml + b_o,
+             kStaticScratchBytes);
+    return ctx->fail(FKV_ENOMEM, msg);
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rcw = wait_recall(ctx, ls, st);
+  if (rcw) return rcw;
+  // the array keeps the last call's contents: the counters must start at zero (a fill kernel, not a
+  // memset node, so that the call can be captured into a graph)
+  launch_fill_zero(reinterpret_cast<int*>(base), heads, st);
+  launch_attn(ctx->dims, ctx->pool_desc(layer), static_cast<const uint16_t*>(q_dev), ctx->ids(layer, ls.parity ^ 1),
+              ctx->ids(layer, ls.parity), ctx->slots(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity),
+              ctx->flags(layer), use, reinterpret_cast<float*>(base + b_cnt + b_ml), reinterpret_cast<float*>(base + b_cnt),
+              n_splits, reinterpret_cast<int*>(base), out_dev, g, st, nullptr, nullptr, nullptr);
+  return after_launch(ctx, "attention kernels (static scratch)");
 }
 
 int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev, int32_t* slot_pages_dev,

@@ -63,6 +63,14 @@ int launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int3
   return a.n_splits;
 }
 
+__global__ __launch_bounds__(256) void fill_zero_kernel(int* __restrict__ p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+void launch_fill_zero(int* p, int n, hipStream_t st) {
+  if (n > 0) fill_zero_kernel<<<(n + 255) / 256, 256, 0, st>>>(p, n);
+}
+
 // ---------------------------------------------------------------------------------
 // The pages a head attends, converted to the NHD layout of the paper's hybrid layouts
 // (Sec. 4.2): out [batch][n_slots][2 (K, V)][page][n_kv][d], slot s of head m = position s of

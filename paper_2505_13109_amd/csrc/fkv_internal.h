@@ -104,6 +104,7 @@ int  launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int
                  const uint8_t* flags, int use, float* part_o, float* part_ml, int max_splits,
                  int* counters, float* out, Geom g, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end,
                  long long* tstamp);
+void launch_fill_zero(int* p, int n, hipStream_t st);       // p[0..n) = 0, by a kernel
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st);
 void launch_export_nhd(const Dims& d, const PoolDesc& pd, const int32_t* act_ids, const int32_t* new_ids,
                        const int32_t* act_slots, const int32_t* new_slots, const uint8_t* flags, int use,
