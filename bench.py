@@ -172,6 +172,10 @@ def main():
     ap.add_argument("--real-layer", action="store_true",
                     help="design-note run: a Llama-shaped layer (QKV, RoPE, o_proj, SwiGLU FFN; random weights, "
                          "library GEMVs) around every layer-step, to see how much recall hides behind real compute")
+    ap.add_argument("--nhd-stream", action="store_true",
+                    help="placement 1: attach an NHD pool, so that every recalled unit is converted on its way in through "
+                         "the recall kernel's two staging buffers (the paper's streamed recall, taken literally) and the "
+                         "pages already on the GPU are converted in place every step")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run a plain elementwise kernel of known size (reads and writes 256 MiB) three "
                          "times: the yardstick for HBM byte counters collected over this command")
@@ -238,6 +242,13 @@ def main():
     out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
     copy_stream = torch.cuda.Stream()
+
+    nhd_attached = None
+    if args.nhd_stream and wl.placement == 1:
+        ns = wl.budget // p + 1
+        nhd_attached = (torch.zeros((wl.batch, ns, 2, p, wl.n_kv_heads, wl.head_dim), dtype=ctx.torch_dtype, device=dev),
+                        torch.zeros((wl.batch, wl.n_kv_heads, ns), dtype=torch.int32, device=dev))
+        ctx.attach_nhd_pool(*nhd_attached)
 
     standin = None
     if args.standin_mb > 0:
@@ -307,6 +318,8 @@ def main():
     # duration plus the dispatch gap, the figure a kernel trace reports
     attn_ms, attn_n = ctx.profile_attn(q[n_steps - 1], out[0], max(1, K // 4), stream=stream)
 
+    if nhd_attached is not None:
+        ctx.attach_nhd_pool(None, None)
     # what the paper's literal GPU layout would add per layer-step: the attended pages converted
     # to an NHD pool (tokens with all KV heads side by side) for a kernel that wants that layout
     n_slots = wl.budget // p + 1
@@ -346,7 +359,8 @@ def main():
                 m = ctx.debug_read(layer, B.DBG_MISS)
                 miss += int(m[..., 0].sum())
                 picked += wl.batch * wl.n_kv_heads * wl.k_pages
-        extra = {"recall_mode": "hipMemcpyAsync per unit" if args.recall_mode else "gather kernel",
+        extra = {"recall_mode": "hipMemcpyAsync per unit" if args.recall_mode else
+                 ("gather kernel, streamed into an NHD pool through two LDS staging buffers" if args.nhd_stream else "gather kernel"),
                  "page_miss_rate": miss / max(picked, 1),
                  "recall_bytes_per_layer_step": miss / max(n_probe * wl.n_layers, 1) * 16384}
         extra["recall_GBps_if_exposed"] = extra["recall_bytes_per_layer_step"] / (elapsed / (K * wl.n_layers)) / 1e9

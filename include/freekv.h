@@ -229,6 +229,24 @@ int fkv_sparse_decode_attn_static(fkv_ctx* ctx, int32_t layer, const void* q_dev
 int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev, int32_t* slot_pages_dev,
                    int32_t n_slots, void* stream);
 
+/* Streamed recall into an NHD pool (Sec. 4.2 "Hybrid layouts" / "Streamed recall"): the paper keeps the GPU
+ * pool in NHD and converts every recalled per-(page, head) unit on its way in, through two staging buffers,
+ * so that the transfer of one unit overlaps the conversion of the one before.  While a pool is attached
+ * (placement HOST, recall_mode GATHER; FKV_ESTATE otherwise), every recall of this context does exactly
+ * that: a recalled unit goes from the pinned host pool into one of two LDS staging buffers of the recall
+ * kernel, from there as 256-byte token rows into the pool (slot = position of the page in its head's attend
+ * list) while the next units' transfers are already in flight -- and, unconverted, into its page-cache slot,
+ * which is what this library's own attention reads.  fkv_decode_step then also converts the pages of Sel(q_i)
+ * that are on the GPU already (sink, window, open page, page-cache hits), so that after the step (and its
+ * deferred recall on the copy stream) the pool holds exactly the attend list of the selection the step
+ * committed, in the format of fkv_export_nhd.
+ *   nhd_pool_dev   dev [batch, n_slots, 2 (K, V), page_size, n_kv, d] of the storage type, 16-byte aligned;
+ *   slot_pages_dev dev [batch, n_kv, n_slots] i32;  n_slots must be budget_tokens / page_size + 1.
+ * The caller owns both and keeps them alive while attached; nhd_pool_dev == NULL detaches.  One pool serves
+ * whichever layer steps (a pool per layer is the caller's to attach before that layer's step).  Host-side
+ * switch, nothing is enqueued. */
+int fkv_attach_nhd_pool(fkv_ctx* ctx, void* nhd_pool_dev, int32_t* slot_pages_dev, int32_t n_slots);
+
 /* End of step (Sec. 3.3: by the end of a step every KV head's Sel(q_i) has been recalled -- corrected
  * heads before attention, the others deferred -- and is what step i+1 reuses): PENDING becomes ACTIVE,
  * the staged query becomes q_prev.  Host-side flip of two buffer halves, nothing is enqueued.

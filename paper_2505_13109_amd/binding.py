@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
     "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
-    "fkv_sparse_decode_attn_static", "fkv_recall_pending", "fkv_test_lose_selection", "fkv_instrument_timestamps",
+    "fkv_sparse_decode_attn_static", "fkv_recall_pending", "fkv_attach_nhd_pool", "fkv_test_lose_selection", "fkv_instrument_timestamps",
 )
 
 
@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         "fkv_page_select": (C.c_int, [vp, i32, vp, vp, vp]),
         "fkv_recall_pages": (C.c_int, [vp, i32, vp, vp, vp]),
         "fkv_recall_pending": (C.c_int, [vp, i32, i32, vp]),
+        "fkv_attach_nhd_pool": (C.c_int, [vp, vp, vp, i32]),
         "fkv_test_lose_selection": (C.c_int, [vp, i32]),
         "fkv_instrument_timestamps": (C.c_int, [vp, i32]),
         "fkv_sparse_decode_attn": (C.c_int, [vp, i32, vp, vp, i32, vp]),
@@ -212,6 +213,12 @@ class FreeKV:
         """nhd_pool [batch, n_slots, 2, page, n_kv, d] storage type, slot_pages [batch, n_kv, n_slots] int32."""
         self._check(self.L.fkv_export_nhd(self._h, layer, use, _ptr(nhd_pool), _ptr(slot_pages),
                                           slot_pages.shape[-1], _stream(stream)), "fkv_export_nhd")
+
+    def attach_nhd_pool(self, nhd_pool, slot_pages):
+        """Streamed recall into this NHD pool from now on (None, None detaches); shapes as in export_nhd."""
+        n_slots = 0 if slot_pages is None else slot_pages.shape[-1]
+        self._nhd_keep = (nhd_pool, slot_pages)          # the library only keeps the addresses
+        self._check(self.L.fkv_attach_nhd_pool(self._h, _ptr(nhd_pool), _ptr(slot_pages), n_slots), "fkv_attach_nhd_pool")
 
     def commit(self, layer):
         self._check(self.L.fkv_commit(self._h, layer), "fkv_commit")

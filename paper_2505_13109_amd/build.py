@@ -20,11 +20,14 @@ FLAGS = [
 
 
 def build(verbose: bool = True, extra_flags=(), lib: str = LIB) -> str:
+    """Compile every source for gfx950 and link `lib`.  Another `lib` (an experiment build with extra
+    flags) keeps its objects beside itself, so it can be built while the product library is."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
+    obj_dir = CSRC if lib == LIB else os.path.dirname(os.path.abspath(lib))
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(obj_dir, os.path.basename(lib) + "." + src.replace(".hip", ".o") if lib != LIB else src.replace(".hip", ".o"))
         cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

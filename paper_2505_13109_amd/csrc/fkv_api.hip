@@ -74,7 +74,7 @@ Layout make_layout(const fkv_config& c) {
   l.ids = o;    o += align_up((size_t)2 * b * n_kv * (l.k > 0 ? l.k : 1) * 4);
   l.slots = o;  o += align_up((size_t)2 * b * n_kv * (l.k > 0 ? l.k : 1) * 4);
   l.flags = o;  o += align_up((size_t)b * n_kv);
-  l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 2 * l.k) * 4);
+  l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 3 * l.k) * 4);   // per head: count, page ids, slots, positions in the picked list
   l.cosine = o; o += align_up((size_t)b * n_q * 8);
   l.counters = o; o += align_up((size_t)(3 * b * n_kv + 1) * 4);   // last-block counters (selection, attention), selection epochs, status
   l.layer_bytes = o;
@@ -141,6 +141,9 @@ struct fkv_ctx {
   std::string err;
   int device = 0;                     // the HIP device the context was created on
   hipEvent_t ev_fork = nullptr;
+  uint16_t* nhd_pool = nullptr;       // fkv_attach_nhd_pool: recalled pages also land, converted, in this NHD pool
+  int32_t* nhd_slot_pages = nullptr;
+  int nhd_slots = 0;
   std::vector<int32_t> host_miss;     // FKV_RECALL_MEMCPY: host copies of the miss lists and flags
   std::vector<uint8_t> host_flags;
   // optional timers around the split attention kernel (fkv_profile_*)
@@ -483,10 +486,11 @@ static int recall_missing(fkv_ctx* ctx, int layer, int heads_mode, const uint8_t
     FKV_HIP(ctx, hipStreamWaitEvent(cs, ls.ev_offload, 0));
   }
   if (ctx->cfg.recall_mode == FKV_RECALL_MEMCPY) {
+    if (ctx->nhd_pool) return ctx->fail(FKV_ESTATE, "the streamed NHD recall needs recall_mode GATHER");
     // the miss lists and flags come to the host (blocking), then one copy per 16 KiB unit
     const fkv_config& c = ctx->cfg;
     const int n_heads = c.batch * c.n_kv_heads, kk = ctx->lay.k;
-    const size_t n_int = (size_t)n_heads * (1 + 2 * kk);
+    const size_t n_int = (size_t)n_heads * (1 + 3 * kk);
     if (ctx->host_miss.size() < n_int) ctx->host_miss.resize(n_int);
     if (ctx->host_flags.size() < (size_t)n_heads) ctx->host_flags.resize(n_heads);
     FKV_HIP(ctx, hipMemcpyAsync(ctx->host_miss.data(), ctx->miss(layer), n_int * 4, hipMemcpyDeviceToHost, cs));
@@ -496,7 +500,7 @@ static int recall_missing(fkv_ctx* ctx, int layer, int heads_mode, const uint8_t
     const PoolDesc pd = ctx->pool_desc(layer);
     for (int h = 0; h < n_heads; ++h) {
       if (heads_mode != FKV_HEADS_ALL && ((heads_mode == FKV_HEADS_FLAGGED) != (ctx->host_flags[h] != 0))) continue;
-      const int32_t* mh = ctx->host_miss.data() + (size_t)h * (1 + 2 * kk);
+      const int32_t* mh = ctx->host_miss.data() + (size_t)h * (1 + 3 * kk);
       for (int i = 0; i < mh[0]; ++i) {
         const uint16_t* src = ctx->host_pool(layer) + ((size_t)h * ctx->lay.max_pages + mh[1 + i]) * UNIT_ELEMS;
         uint16_t* dst = pd.pool + ((size_t)h * pd.units_per_head + pd.sel_base + mh[1 + kk + i]) * UNIT_ELEMS;
@@ -504,6 +508,12 @@ static int recall_missing(fkv_ctx* ctx, int layer, int heads_mode, const uint8_t
       }
     }
     return FKV_OK;
+  }
+  if (ctx->nhd_pool) {
+    // streamed recall: host unit -> LDS staging -> page-cache slot and NHD rows (Sec. 4.2)
+    launch_gather_nhd(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ctx->miss(layer), select_by, heads_mode,
+                      ctx->nhd_pool, ctx->nhd_slots, make_geom(ctx->cfg, ls.L).n_sink, cs);
+    return after_launch(ctx, "streamed NHD gather kernel");
   }
   launch_gather(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ctx->miss(layer), nullptr,
                 select_by, heads_mode, cs);
@@ -632,6 +642,24 @@ int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev,
   return after_launch(ctx, "NHD export kernel");
 }
 
+int fkv_attach_nhd_pool(fkv_ctx* ctx, void* nhd_pool_dev, int32_t* slot_pages_dev, int32_t n_slots) {
+  if (!ctx) return FKV_EINVAL;
+  if (!nhd_pool_dev) {
+    ctx->nhd_pool = nullptr; ctx->nhd_slot_pages = nullptr; ctx->nhd_slots = 0;
+    return FKV_OK;
+  }
+  const fkv_config& c = ctx->cfg;
+  if (c.placement != FKV_PLACE_HOST) return ctx->fail(FKV_ESTATE, "the streamed NHD recall is for the host-pool placement");
+  if (c.recall_mode != FKV_RECALL_GATHER) return ctx->fail(FKV_ESTATE, "the streamed NHD recall needs recall_mode GATHER");
+  if (!slot_pages_dev) return ctx->fail(FKV_EINVAL, "null slot_pages");
+  if (n_slots != c.budget_tokens / c.page_size + 1) return ctx->fail(FKV_EINVAL, "n_slots must be budget/page + 1");
+  if ((reinterpret_cast<uintptr_t>(nhd_pool_dev) & 15) != 0) return ctx->fail(FKV_EINVAL, "pool not 16-byte aligned");
+  ctx->nhd_pool = static_cast<uint16_t*>(nhd_pool_dev);
+  ctx->nhd_slot_pages = slot_pages_dev;
+  ctx->nhd_slots = n_slots;
+  return FKV_OK;
+}
+
 int fkv_commit(fkv_ctx* ctx, int32_t layer) {
   FKV_CHECK_LAYER(ctx, layer);
   LayerState& ls = ctx->layers[layer];
@@ -720,6 +748,15 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   }
   rc = fkv_sparse_decode_attn(ctx, layer, q_dev, out_dev, FKV_USE_BY_FLAG, compute_stream);
   if (rc) return rc;
+  if (host_pool && ctx->nhd_pool) {
+    // the literal NHD pool: the pages of Sel(q_i) that are on the GPU already (sink, window, open page, page-cache
+    // hits) are converted in place; the missing ones arrive through the streamed recall
+    launch_export_nhd(ctx->dims, ctx->pool_desc(layer), ctx->ids(layer, ls.parity ^ 1), ctx->ids(layer, ls.parity),
+                      ctx->slots(layer, ls.parity ^ 1), ctx->slots(layer, ls.parity), ctx->flags(layer), FKV_USE_PENDING,
+                      ctx->nhd_pool, ctx->nhd_slot_pages, ctx->nhd_slots, make_geom(ctx->cfg, ls.L), st, ctx->miss(layer));
+    rc = after_launch(ctx, "NHD export kernel");
+    if (rc) return rc;
+  }
   if (host_pool && cs == st) {
     rc = fkv_recall_pending(ctx, layer, FKV_HEADS_UNFLAGGED, compute_stream);
     if (rc) return rc;
@@ -854,11 +891,11 @@ int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, si
       n = (size_t)c.batch * c.n_kv_heads * (1 + kk) * 4;
       if (bytes < n) return ctx->fail(FKV_EINVAL, "output buffer too small");
       FKV_HIP(ctx, hipDeviceSynchronize());
-      std::vector<int32_t> tmp((size_t)c.batch * c.n_kv_heads * (1 + 2 * kk));
+      std::vector<int32_t> tmp((size_t)c.batch * c.n_kv_heads * (1 + 3 * kk));
       FKV_HIP(ctx, hipMemcpy(tmp.data(), ctx->miss(layer), tmp.size() * 4, hipMemcpyDeviceToHost));
       int32_t* o = static_cast<int32_t*>(host_out);
       for (int h = 0; h < c.batch * c.n_kv_heads; ++h) {
-        const int32_t* mh = tmp.data() + (size_t)h * (1 + 2 * kk);
+        const int32_t* mh = tmp.data() + (size_t)h * (1 + 3 * kk);
         o[(size_t)h * (1 + kk)] = mh[0];
         for (size_t i = 0; i < kk; ++i) o[(size_t)h * (1 + kk) + 1 + i] = (int32_t)i < mh[0] ? mh[1 + i] : -1;
       }

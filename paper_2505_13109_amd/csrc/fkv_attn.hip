@@ -77,9 +77,14 @@ void launch_fill_zero(int* p, int n, hipStream_t st) {
 // m's attend list; slot_pages [batch][n_kv][n_slots].  One block per (slot, head): the 16 KiB
 // unit comes in with linear 16-byte loads, is turned in LDS, and goes out as 256-byte token rows.
 // ---------------------------------------------------------------------------------
+// `miss` (may be null): the recall plan's miss lists [heads][1 + 3k].  With it, a picked page that the
+// plan marked missing is left alone -- its rows arrive through the streamed recall -- and only its
+// page id is recorded.
 __global__ __launch_bounds__(256) void export_nhd_kernel(AttnArgs a, uint16_t* __restrict__ out,
-                                                         int32_t* __restrict__ slot_pages, int n_slots) {
+                                                         int32_t* __restrict__ slot_pages, int n_slots,
+                                                         const int32_t* __restrict__ miss) {
   __shared__ __attribute__((aligned(16))) uint16_t unit_lds[UNIT_ELEMS];
+  __shared__ int s_missing;
   const int slot = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
   const int head = b * a.n_kv + m, k = a.k;
   const Geom& g = a.g;
@@ -94,6 +99,15 @@ __global__ __launch_bounds__(256) void export_nhd_kernel(AttnArgs a, uint16_t* _
   if (slot < n_att) unit = attend_unit(al, a.pd, slot, n_valid, page);
   if (unit < 0) { page = -1; n_valid = 0; }
   if (threadIdx.x == 0) slot_pages[(size_t)head * n_slots + slot] = page;
+  if (miss && unit >= 0 && slot >= g.n_sink && slot < g.n_sink + k) {
+    if (threadIdx.x == 0) s_missing = 0;
+    __syncthreads();
+    const int32_t* mh = miss + (size_t)head * (1 + 3 * k);
+    for (int r = threadIdx.x; r < mh[0]; r += 256)
+      if (mh[1 + 2 * k + r] == slot - g.n_sink) s_missing = 1;
+    __syncthreads();
+    if (s_missing) return;
+  }
   if (unit >= 0) {
     const uint4* src = reinterpret_cast<const uint4*>(a.pd.pool + ((size_t)head * a.pd.units_per_head + unit) * UNIT_ELEMS);
     uint4* dst = reinterpret_cast<uint4*>(unit_lds);
@@ -123,12 +137,12 @@ __global__ __launch_bounds__(256) void export_nhd_kernel(AttnArgs a, uint16_t* _
 
 void launch_export_nhd(const Dims& d, const PoolDesc& pd, const int32_t* act_ids, const int32_t* new_ids,
                        const int32_t* act_slots, const int32_t* new_slots, const uint8_t* flags, int use,
-                       uint16_t* out, int32_t* slot_pages, int n_slots, Geom g, hipStream_t st) {
+                       uint16_t* out, int32_t* slot_pages, int n_slots, Geom g, hipStream_t st, const int32_t* skip_missing) {
   AttnArgs a{};
   a.pd = pd; a.act_ids = act_ids; a.new_ids = new_ids; a.act_slots = act_slots; a.new_slots = new_slots;
   a.flags = flags; a.use = use; a.g = g; a.n_q = d.n_q; a.n_kv = d.n_kv; a.G = d.G; a.k = d.k;
   dim3 grid(n_slots, d.n_kv, d.batch);
-  export_nhd_kernel<<<grid, 256, 0, st>>>(a, out, slot_pages, n_slots);
+  export_nhd_kernel<<<grid, 256, 0, st>>>(a, out, slot_pages, n_slots, skip_missing);
 }
 
 }  // namespace fkv

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void offload_kernel(PoolDesc pd, uint16_t* __r
 }
 
 // ---- recall: copy missing pages host pool -> free page-cache slots ---------------
-// miss: [heads][1 + 2k] = count, then k page ids, then k slots.
+// miss: [heads][1 + 3k] = count, then k page ids, k slots, k positions in the picked list.
 // A few 1024-thread blocks share the miss lists, four 16 KiB units in flight per block.  Loads
 // from host memory take microseconds to return and hold up the memory pipeline of the compute
 // unit they are issued from, so the blocks are kept few and each one claims a whole compute
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, con
   // serves about every other head, with anything from 0 to k misses).
   for (int head = tid; head < n_heads; head += GATHER_THREADS) {
     const bool chosen = heads_mode == 0 || ((heads_mode == 1) == (flags[head] != 0));
-    chunks_of[head] = chosen ? (miss[(size_t)head * (1 + 2 * k)] + GATHER_UNITS - 1) / GATHER_UNITS : 0;
+    chunks_of[head] = chosen ? (miss[(size_t)head * (1 + 3 * k)] + GATHER_UNITS - 1) / GATHER_UNITS : 0;
   }
   __syncthreads();
   int first = 0;                                // number of the head's first chunk
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, con
     // chunks of this head that are this block's: c_begin + j with (c_begin + j) % gridDim.x == blockIdx.x
     int j = ((int)blockIdx.x - c_begin % (int)gridDim.x + (int)gridDim.x) % (int)gridDim.x;
     if (j >= n_chunks) continue;
-    const int32_t* mh = miss + (size_t)head * (1 + 2 * k);
+    const int32_t* mh = miss + (size_t)head * (1 + 3 * k);
     const int n = mh[0];
     const uint16_t* src_head = host_pool + (size_t)head * max_pages * UNIT_ELEMS;
     uint16_t* dst_head = pd.pool + ((size_t)head * pd.units_per_head + pd.sel_base) * UNIT_ELEMS;
@@ -154,6 +154,103 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, con
         if (i0 + u < n) reinterpret_cast<uint4*>(dst_head + (size_t)mh[1 + k + i0 + u] * UNIT_ELEMS)[tid] = w[u];
       }
     }
+  }
+}
+
+// ---- streamed recall into an NHD pool (Sec. 4.2 "Hybrid layouts", "Streamed recall") -------------
+// The paper keeps the GPU pool in NHD (tokens with all KV heads side by side) and the host pool in
+// per-(page, head) units; a recalled unit is turned into NHD on its way in, through two staging
+// buffers, so that the transfer of one unit overlaps the conversion of the previous one.  Here the
+// staging buffers are two LDS buffers of GATHER_UNITS units per block: while the block turns the
+// units of buffer A into 256-byte token rows of the pool, the loads of its next units from the
+// pinned host pool are already in flight, and land in buffer B.  The unit also goes, unconverted,
+// to its page-cache slot (what this library's own attention reads, and what makes the page a hit
+// at the next step).  nhd: [batch][n_slots][2 (K, V)][PG][n_kv][D]; a miss at position i of its
+// head's picked list goes to pool slot n_sink + i.
+__global__ __launch_bounds__(GATHER_THREADS) void gather_nhd_kernel(PoolDesc pd, const uint16_t* __restrict__ host_pool,
+                                                                    const int32_t* __restrict__ miss,
+                                                                    const uint8_t* __restrict__ flags, int heads_mode,
+                                                                    int k, int n_kv, int n_heads, int max_pages,
+                                                                    uint16_t* __restrict__ nhd, int n_slots, int n_sink) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
+  uint16_t* stage = reinterpret_cast<uint16_t*>(gsm);                                   // [2][GATHER_UNITS][UNIT_ELEMS]
+  int32_t* chunks_of = reinterpret_cast<int32_t*>(gsm + 2 * GATHER_UNITS * UNIT_BYTES);   // [n_heads]
+  const int tid = threadIdx.x;
+  for (int head = tid; head < n_heads; head += GATHER_THREADS) {
+    const bool chosen = heads_mode == 0 || ((heads_mode == 1) == (flags[head] != 0));
+    chunks_of[head] = chosen ? (miss[(size_t)head * (1 + 3 * k)] + GATHER_UNITS - 1) / GATHER_UNITS : 0;
+  }
+  __syncthreads();
+  // this block's chunks, in order: chunk c of the launch-wide numbering is ours iff c % gridDim.x == blockIdx.x
+  struct Cursor { int head, first, j; };          // head, number of its first chunk, chunk within the head
+  auto advance = [&](Cursor& c) -> bool {         // to this block's next chunk; false when there is none
+    for (;;) {
+      if (c.head >= n_heads) return false;
+      const int n_chunks = chunks_of[c.head];
+      if (c.j < 0) c.j = ((int)blockIdx.x - c.first % (int)gridDim.x + (int)gridDim.x) % (int)gridDim.x;
+      else c.j += gridDim.x;
+      if (c.j < n_chunks) return true;
+      c.first += n_chunks;
+      c.head += 1;
+      c.j = -1;
+    }
+  };
+  auto load = [&](const Cursor& c, uint4* w) {
+    const int32_t* mh = miss + (size_t)c.head * (1 + 3 * k);
+    const int n = mh[0];
+    const uint16_t* src_head = host_pool + (size_t)c.head * max_pages * UNIT_ELEMS;
+#pragma unroll
+    for (int u = 0; u < GATHER_UNITS; ++u) {
+      const int i = min(c.j * GATHER_UNITS + u, n - 1);
+      w[u] = reinterpret_cast<const uint4*>(src_head + (size_t)mh[1 + i] * UNIT_ELEMS)[tid];
+    }
+  };
+  Cursor cur{0, 0, -1};
+  bool have = advance(cur);
+  uint4 w[GATHER_UNITS];
+  if (have) load(cur, w);
+  int buf = 0;
+  while (have) {
+    const int32_t* mh = miss + (size_t)cur.head * (1 + 3 * k);
+    const int n = mh[0], i0 = cur.j * GATHER_UNITS;
+    uint16_t* dst_head = pd.pool + ((size_t)cur.head * pd.units_per_head + pd.sel_base) * UNIT_ELEMS;
+    uint16_t* st_buf = stage + (size_t)buf * GATHER_UNITS * UNIT_ELEMS;
+#pragma unroll
+    for (int u = 0; u < GATHER_UNITS; ++u) {
+      if (i0 + u < n) {
+        reinterpret_cast<uint4*>(dst_head + (size_t)mh[1 + k + i0 + u] * UNIT_ELEMS)[tid] = w[u];    // page-cache slot
+        reinterpret_cast<uint4*>(st_buf + (size_t)u * UNIT_ELEMS)[tid] = w[u];                         // staging buffer
+      }
+    }
+    // the next chunk's transfer starts now and runs during the conversion below
+    const Cursor done = cur;
+    have = advance(cur);
+    if (have) load(cur, w);
+    __syncthreads();
+    // conversion: unit u of the staging buffer -> 2 x PG token rows of 16 chunks of 8 channels
+    const int b = done.head / n_kv, m = done.head % n_kv;
+#pragma unroll
+    for (int u = 0; u < GATHER_UNITS; ++u) {
+      if (i0 + u >= n) break;
+      const int slot = n_sink + mh[1 + 2 * k + i0 + u];
+      const uint16_t* unit = st_buf + (size_t)u * UNIT_ELEMS;
+      for (int i = tid; i < 2 * PG * (D / 8); i += GATHER_THREADS) {
+        const int c8 = i % (D / 8), t = (i / (D / 8)) % PG, kv = i / (D / 8) / PG;
+        uint4 o;
+        if (kv == 0) {
+          o = *reinterpret_cast<const uint4*>(unit + k_elem_off(t, c8 * 8));        // 8 channels lie together
+        } else {
+          uint16_t e[8];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) e[c] = unit[v_elem_off(t, c8 * 8 + c)];
+          o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
+          o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
+        }
+        uint16_t* row = nhd + ((((size_t)(b * n_slots + slot) * 2 + kv) * PG + t) * n_kv + m) * D;
+        *reinterpret_cast<uint4*>(row + c8 * 8) = o;
+      }
+    }
+    buf ^= 1;      // the buffer just converted is written again two chunks on, behind the next barrier
   }
 }
 
@@ -177,7 +274,7 @@ __global__ __launch_bounds__(64) void plan_kernel(int32_t* __restrict__ new_ids,
   int32_t* freelist = nslot + k;
   const int m = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
   const size_t hb = (size_t)(b * n_kv + m) * k;
-  int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 2 * k);
+  int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 3 * k);
   for (int s = lane; s < 2 * k; s += 64) used[s] = 0;
   int n_act = 0;
   for (int i = lane; i < k; i += 64) {     // all lists in one round trip
@@ -229,6 +326,7 @@ __global__ __launch_bounds__(64) void plan_kernel(int32_t* __restrict__ new_ids,
       nslot[i] = s;
       mh[1 + r] = nid[i];
       mh[1 + k + r] = s;
+      mh[1 + 2 * k + r] = i;
     }
     n_miss += (int)__builtin_amdgcn_readlane((int)incl, 63);
   }
@@ -291,6 +389,23 @@ void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool,
   const int n_heads = d.batch * d.n_kv;
   const int blocks = n_heads < GATHER_BLOCKS ? n_heads : GATHER_BLOCKS;
   gather_kernel<<<blocks, GATHER_THREADS, hog, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, n_heads, d.max_pages);
+}
+
+void launch_gather_nhd(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
+                       const uint8_t* flags, int heads, uint16_t* nhd, int n_slots, int n_sink, hipStream_t st) {
+  if (d.k == 0) return;
+  static bool raised = false;
+  const int n_heads = d.batch * d.n_kv;
+  const size_t lds = (size_t)2 * GATHER_UNITS * UNIT_BYTES + (size_t)n_heads * sizeof(int32_t);   // 128 KiB of staging: the unit's LDS is taken anyway
+  if (!raised) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_nhd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              d.max_lds > 64 * 1024 ? d.max_lds - 1024 : 64 * 1024 - 1024);
+    (void)hipGetLastError();
+    raised = true;
+  }
+  const int blocks = n_heads < GATHER_BLOCKS ? n_heads : GATHER_BLOCKS;
+  gather_nhd_kernel<<<blocks, GATHER_THREADS, lds, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, n_heads, d.max_pages,
+                                                          nhd, n_slots, n_sink);
 }
 
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st) {

@@ -108,6 +108,10 @@ void launch_fill_zero(int* p, int n, hipStream_t st);       // p[0..n) = 0, by a
 void launch_read_page(const uint16_t* unit, uint16_t* out_token_major, hipStream_t st);
 void launch_export_nhd(const Dims& d, const PoolDesc& pd, const int32_t* act_ids, const int32_t* new_ids,
                        const int32_t* act_slots, const int32_t* new_slots, const uint8_t* flags, int use,
-                       uint16_t* out, int32_t* slot_pages, int n_slots, Geom g, hipStream_t st);
+                       uint16_t* out, int32_t* slot_pages, int n_slots, Geom g, hipStream_t st,
+                       const int32_t* skip_missing = nullptr);   // miss lists: leave the pages they name to the streamed recall
+// recall of the missing pages into their page-cache slots AND, converted, into an NHD pool
+void launch_gather_nhd(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
+                       const uint8_t* flags, int heads, uint16_t* nhd, int n_slots, int n_sink, hipStream_t st);
 
 }  // namespace fkv

@@ -14,7 +14,7 @@ namespace fkv {
 // only if its role bit is set; heads = batch * n_kv.
 // ---------------------------------------------------------------------------------
 template <int DT, int G>
-__global__ __launch_bounds__(STEP_THREADS) void step_kernel(StepArgs a) {
+__global__ __launch_bounds__(STEP_THREADS, STEP_THREADS <= 256 ? 2 : 1) void step_kernel(StepArgs a) {
   extern __shared__ uint32_t dyn_lds[];              // selection: n_cand keys, then G x n_cand weights
   step_roles<DT, G, false>(a, blockIdx.x, dyn_lds);
 }
@@ -146,7 +146,9 @@ int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t 
       passes *= 2;
   // ... and beyond a few blocks per unit, a block takes several chunks in turn: a block's fixed cost
   // (dispatch, the query loads, the drain of its stores) is what is left to save once the scan
-  // streams
+  // streams.  (Prefetching the next chunk into a second register set was measured and dropped: the
+  // registers it takes halve the blocks a unit holds, and two blocks that load and compute in turn
+  // stream faster than one that overlaps its own loads.)
   int chunks_per_block = g_chunks_per_block > 0 ? g_chunks_per_block : 1;
   if (g_chunks_per_block <= 0 && (roles & ROLE_SELECT)) {
     const long blocks = (long)d.batch * d.n_kv * ((g.n_cand + PAGES_PER_PASS * passes - 1) / (PAGES_PER_PASS * passes));
@@ -172,7 +174,7 @@ struct LayerArgs {
 };
 
 template <int DT, int G>
-__global__ __launch_bounds__(STEP_THREADS) void layer_kernel(LayerArgs a) {
+__global__ __launch_bounds__(STEP_THREADS, STEP_THREADS <= 256 ? 2 : 1) void layer_kernel(LayerArgs a) {
   extern __shared__ uint32_t dyn_lds[];
   if ((int)blockIdx.x < a.attn_block0) {
     step_roles<DT, G, true>(a.s, blockIdx.x, dyn_lds);

@@ -507,6 +507,49 @@ def test_nhd_export_of_the_attended_pages():
     pr.close()
 
 
+def test_streamed_recall_into_an_nhd_pool():
+    """Sec. 4.2 "Streamed recall" taken literally: with an NHD pool attached, every recalled unit passes through
+    the recall kernel's two staging buffers and lands converted in the pool (and unconverted in its page-cache
+    slot), the pages already on the GPU are converted in place.  After every step the pool must equal the
+    oracle's NHD pool of the selection the step committed, byte for byte; ids, flags and attention stay exact."""
+    wl = W.get_workload("c3").scaled(batch=2, ctx=8192 - 3, steps=48)
+    pr = _pair(wl, [9], steps=48)
+    n_slots = wl.budget // wl.page_size + 1
+    pool = torch.full((wl.batch, n_slots, 2, wl.page_size, wl.n_kv_heads, wl.head_dim), 7.0, dtype=pr.g.torch_dtype, device="cuda")
+    pages = torch.full((wl.batch, wl.n_kv_heads, n_slots), -7, dtype=torch.int32, device="cuda")
+    pr.g.attach_nhd_pool(pool, pages)
+    for t in range(48):
+        pr.step(0, t, deep=False)
+        torch.cuda.synchronize()                           # the deferred recall on the copy stream included
+        got = W.decode(pool.view(torch.int16).cpu().numpy().view(np.uint16), wl.dtype)
+        for r in range(wl.batch):
+            o = pr.oracles[(0, r)]
+            ref_pool, ref_pages = o.export_nhd(o.active, n_slots)
+            assert np.array_equal(pages.cpu().numpy()[r], ref_pages), f"slot pages differ: step {t} request {r}"
+            assert np.array_equal(got[r], ref_pool), f"NHD pool differs: step {t} request {r}"
+    assert pr.stats["misses"] > 100 and 0 < pr.stats["flagged"] < pr.stats["heads"]
+    pr.g.attach_nhd_pool(None, None)
+    pr.close()
+    # growing context in fp16 with G = 5: empty slots, the first candidates, the first recalls
+    wl = W.Workload("nhdgrow", 1, 2, 10, 2, "fp16", 40, 256, 32, 64, 0.75, 200, 0.75, 0.66, 83, placement=1, shift_every=70)
+    pr = _pair(wl, [1])
+    n_slots = wl.budget // wl.page_size + 1
+    pool = torch.zeros((wl.batch, n_slots, 2, wl.page_size, wl.n_kv_heads, wl.head_dim), dtype=pr.g.torch_dtype, device="cuda")
+    pages = torch.zeros((wl.batch, wl.n_kv_heads, n_slots), dtype=torch.int32, device="cuda")
+    pr.g.attach_nhd_pool(pool, pages)
+    for t in range(wl.steps):
+        pr.step(0, t, deep=False)
+        if t % 7 == 0 or t > wl.steps - 4:
+            torch.cuda.synchronize()
+            got = W.decode(pool.view(torch.int16).cpu().numpy().view(np.uint16), wl.dtype)
+            for r in range(wl.batch):
+                o = pr.oracles[(0, r)]
+                ref_pool, ref_pages = o.export_nhd(o.active, n_slots)
+                assert np.array_equal(pages.cpu().numpy()[r], ref_pages) and np.array_equal(got[r], ref_pool), (t, r)
+    assert pr.stats["misses"] > 0
+    pr.close()
+
+
 def test_a_wait_that_runs_out_is_reported():
     """The bounded wait of a corrected head's attention: with the library's test hook on, the waves that
     attend picked pages wait for an announcement that never comes.  Every kernel still ends; the failure
