@@ -217,7 +217,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     p = wl.page_size
-    max_ctx = ((wl.ctx + 2 * n_steps + 16 + p - 1) // p) * p   # the steps are run twice (timed, then with kernel timers)
+    long_run = K > 2048                        # a long generation: one pass, timed in segments, no per-launch event pass
+    max_ctx = ((wl.ctx + (1 if long_run else 2) * n_steps + 16 + p - 1) // p) * p   # the steps are run twice (timed, then with kernel timers)
     ctx = fkv.FreeKV(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
                      max_ctx=max_ctx, budget=wl.budget, sink=wl.sink, window=wl.window, tau=wl.tau,
                      dtype=wl.dtype, placement=wl.placement, recall_mode=args.recall_mode)
@@ -255,42 +256,26 @@ def main():
         standin = torch.ones(args.standin_mb * 1000 * 1000 // 2, dtype=torch.bfloat16, device=dev)
         sink_val = torch.zeros((1,), dtype=torch.float32, device=dev)
 
-    real = None
+    stack = None
     if args.real_layer:
-        # The rest of a decoder layer, for its cost and its place on the stream only: hidden = n_q * d,
-        # FFN 3.5 x hidden (Llama-3.1-8B: 4096 / 14336, 436 MB of weights per layer), random weights,
-        # distinct per layer.  The loop's own q, k, v stay the seeded synthetic streams, so that the reuse
+        # The rest of a decoder layer, for its cost and its place on the stream (paper_2505_13109_amd/layer_loop.py):
+        # hidden = n_q * d, FFN 3.5 x hidden (Llama-3.1-8B: 4096 / 14336, 436 MB of weights per layer), random
+        # weights, distinct per layer.  The loop's own q, k, v stay the seeded synthetic streams, so that the reuse
         # and correction statistics remain the workload's; the projections are computed and dropped.
-        hid, ffn, dt = wl.n_q_heads * wl.head_dim, int(3.5 * wl.n_q_heads * wl.head_dim), ctx.torch_dtype
-        qkv_out = (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim
-        g = torch.Generator(device=dev).manual_seed(7)
-        mk = lambda *s: (torch.randn(*s, generator=g, device=dev, dtype=torch.float32) * 0.02).to(dt)
-        real = {"wqkv": [mk(hid, qkv_out) for _ in range(wl.n_layers)], "wo": [mk(hid, hid) for _ in range(wl.n_layers)],
-                "wgu": [mk(hid, 2 * ffn) for _ in range(wl.n_layers)], "wd": [mk(ffn, hid) for _ in range(wl.n_layers)],
-                "x": mk(wl.batch, hid) * 50, "cos": mk(1, 1, wl.head_dim // 2) * 50, "sin": mk(1, 1, wl.head_dim // 2) * 50,
-                "weight_MB_per_layer": (hid * qkv_out + hid * hid + 3 * hid * ffn) * 2 / 1e6}
-
-        def rms(x):
-            return x * torch.rsqrt(x.float().pow(2).mean(-1, keepdim=True) + 1e-5).to(x.dtype)
-
-        def rope(x):
-            a, b2 = x[..., : wl.head_dim // 2], x[..., wl.head_dim // 2:]
-            return torch.cat([a * real["cos"] - b2 * real["sin"], a * real["sin"] + b2 * real["cos"]], dim=-1)
+        from paper_2505_13109_amd.layer_loop import DecoderStack
+        stack = DecoderStack(ctx, copy_stream=copy_stream)
+        stack.out = out
+        x_in = (torch.randn((wl.batch, stack.hidden), device=dev) ).to(ctx.torch_dtype)
 
     def run(t0, t1):
         for t in range(t0, t1):
-            x = real["x"] if real else None
+            if stack is not None:
+                stack.step(x_in, external_qkv=[(q[t, layer], k_new[t, layer], v_new[t, layer]) for layer in range(wl.n_layers)],
+                           stream=stream)
+                continue
             for layer in range(wl.n_layers):
-                if real:
-                    qkv = (rms(x) @ real["wqkv"][layer]).view(wl.batch, -1, wl.head_dim)
-                    rope(qkv[:, : wl.n_q_heads + wl.n_kv_heads])
                 ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer],
                                 stream=stream, copy_stream=copy_stream)
-                if real:
-                    x = x + out[layer].to(x.dtype).view(wl.batch, -1) @ real["wo"][layer]
-                    gu = rms(x) @ real["wgu"][layer]
-                    half = gu.shape[-1] // 2
-                    x = x + (torch.nn.functional.silu(gu[:, :half]) * gu[:, half:]) @ real["wd"][layer]
                 if standin is not None:
                     torch.sum(standin, dim=(0,), keepdim=True, dtype=torch.float32, out=sink_val)
 
@@ -299,7 +284,20 @@ def main():
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_begin = time.perf_counter()
     ev0.record(stream)                     # HIP events on the launch stream, around the timed region
-    run(Wm, n_steps)
+    if not long_run:
+        run(Wm, n_steps)
+    seg_events = []
+    if long_run:                               # the timed steps in 16 segments, an event at every boundary
+        seg = max(1, K // 16)
+        t0 = Wm
+        while t0 < n_steps:
+            t1 = min(n_steps, t0 + seg)
+            run(t0, t1)
+            e = torch.cuda.Event(enable_timing=True)
+            e.record(stream)
+            seg_events.append((t1 - t0, e))
+            t0 = t1
+            print(f"bench.py: {t0 - Wm} of {K} timed steps enqueued, {time.perf_counter() - t_begin:.0f} s", file=sys.stderr, flush=True)
     ev1.record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
@@ -309,10 +307,20 @@ def main():
 
     # second pass over the same step inputs with a HIP event pair around every launch of the
     # split attention kernel (the dominant HBM reader), on the stream it is launched on
-    ctx.profile_enable(K * wl.n_layers)
-    run(Wm, n_steps)
-    pair_ms, pair_n = ctx.profile_read()
-    ctx.profile_enable(0)
+    pair_ms, pair_n = 0.0, 0
+    if not long_run:
+        ctx.profile_enable(K * wl.n_layers)
+        run(Wm, n_steps)
+        pair_ms, pair_n = ctx.profile_read()
+        ctx.profile_enable(0)
+    segments = {}
+    if seg_events:
+        prev, ctx_at, rows = ev0, wl.ctx + Wm, []
+        for n, e in seg_events:
+            ctx_at += n
+            rows.append({"ctx_at_end": ctx_at, "ms_per_step": prev.elapsed_time(e) / n})
+            prev = e
+        segments = {"ms_per_step_by_segment": rows}
     # and the same kernel launched back to back for every layer in turn between ONE event
     # pair: no marker sits between a launch and the next, so the average is the kernel's
     # duration plus the dispatch gap, the figure a kernel trace reports
@@ -416,7 +424,7 @@ def main():
                    **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}),
                    **({"real_layer": "QKV + RoPE + o_proj + SwiGLU FFN GEMVs with random weights around every layer-step "
                                      "(library GEMVs; the loop's q, k, v stay the synthetic streams)",
-                       "real_layer_weight_MB": real["weight_MB_per_layer"]} if real else {}), **extra, **prefill, **nhd},
+                       "real_layer_weight_MB": stack.weight_bytes_per_layer / 1e6} if stack else {}), **segments, **extra, **prefill, **nhd},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,

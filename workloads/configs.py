@@ -68,6 +68,11 @@ WORKLOADS = {
     # long generation: G = 7, context grows 2048 -> 34816, topic shift every 1024 steps
     "c5": Workload("c5", 28, 1, 28, 4, "bf16", 2048, 2048, 512, 512, 0.9, 32768, 0.7, _noise(0.7), 4,
                    shift_every=1024),
+    # the paper's long-generation scenario (Sec. 5.3 "Setup": 600 tokens in, 16K out, B = 2048, S = W = 512,
+    # tau = 0.9) on the Llama-3.1-8B shape with the KV pool in host memory; rho inside the similarity range the
+    # paper reports (Table 8), so that a part of the heads is corrected each step as in its Table 9
+    "longgen": Workload("longgen", 32, 1, 32, 8, "bf16", 600, 2048, 512, 512, 0.9, 16384, 0.93, _noise(0.93), 5,
+                        placement=1),
 }
 
 
