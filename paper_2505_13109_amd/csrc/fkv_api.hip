@@ -49,7 +49,7 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
   // per layer
-  size_t pool, summ, qprev, ids, slots, flags, miss, cosine, counters, layer_bytes;
+  size_t pool, summ, qprev, ids, slots, flags, miss, cosine, counters, tagged, layer_bytes;
   // per context
   size_t P, score, part_o, part_ml, dbg_page, tstamp, ctx_bytes;
   size_t total;
@@ -77,6 +77,7 @@ Layout make_layout(const fkv_config& c) {
   l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 3 * l.k) * 4);   // per head: count, page ids, slots, positions in the picked list
   l.cosine = o; o += align_up((size_t)b * n_q * 8);
   l.counters = o; o += align_up((size_t)(3 * b * n_kv + 1) * 4);   // last-block counters (selection, attention), selection epochs, status
+  l.tagged = o; o += align_up((size_t)b * n_kv * (l.k > 0 ? l.k : 1) * 8);   // epoch-tagged copies of the picked ids (one-launch layer-step)
   l.layer_bytes = o;
   size_t p = 0;
   l.P = p;       p += align_up((size_t)b * n_q * l.max_pages * 4);
@@ -173,7 +174,7 @@ struct fkv_ctx {
   double* cosine(int l) const { return reinterpret_cast<double*>(layer_base(l) + lay.cosine); }
   int* sel_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters); }
   int* attn_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + cfg.batch * cfg.n_kv_heads; }
-  int* sel_done(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + 2 * cfg.batch * cfg.n_kv_heads; }
+  unsigned long long* tagged(int l) const { return reinterpret_cast<unsigned long long*>(layer_base(l) + lay.tagged); }
   int* status(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + 3 * cfg.batch * cfg.n_kv_heads; }
   float* P() const { return reinterpret_cast<float*>(ctx_base() + lay.P); }
   float* score() const { return reinterpret_cast<float*>(ctx_base() + lay.score); }
@@ -695,7 +696,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     lio.max_splits = ctx->lay.max_splits;
     lio.attn_counters = ctx->attn_counters(layer);
     lio.out = out_dev;
-    lio.sel_done = ctx->sel_done(layer);
+    lio.tagged = ctx->tagged(layer);
     lio.epoch = ls.epoch + 1;
     lio.status = ctx->status(layer);
     lio.attn_epoch_bias = ctx->lose_selection ? 1 : 0;

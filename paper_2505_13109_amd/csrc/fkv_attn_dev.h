@@ -85,7 +85,7 @@ struct AttnArgs {
   int corr_pool;
   const uint16_t* k_new;
   const uint16_t* v_new;
-  const int* sel_done;       // [heads]: epoch of the last finished selection
+  const unsigned long long* tagged;   // [heads][k]: this step's picked ids as (epoch << 32 | id), written by the selection
   int epoch;
   int* status;               // set to 1 if a wait ran out
 };
@@ -208,31 +208,34 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
     auto find = [&](int from, int& nv, int& pg) -> int2 {
       for (int p2 = from; p2 < p_end; p2 += NW) {
         if (two_phase && ((p2 >= pk_lo && p2 < pk_hi) != (phase == 1))) continue;
-        const int u = attend_unit(al, pd, p2, nv, pg, spec && !pending && p2 == pos0, spec_id);
+        bool have_id = spec && !pending && p2 == pos0;
+        int id = spec_id;
+        if (two_phase && phase == 1) {
+          // Wait for this step's id of the position: the selection writes every picked id as one 64-bit
+          // word tagged with the step's epoch.  The block that makes it is one of the scoring blocks of
+          // this launch, which all have lower block indices than any attention block and never wait for
+          // anything, so it is running or done; the wait is bounded all the same.  The whole wave polls
+          // the same word (one request per poll).
+          if (timed_out) break;
+          const unsigned long long* word = a.tagged + (size_t)head * k + (p2 - pk_lo);
+          unsigned long long w2;
+          int it = 0;
+          while (((w2 = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != (unsigned long long)(uint32_t)a.epoch) {
+            if (++it > (1 << 16)) { timed_out = true; break; }   // ~0.1 s
+            __builtin_amdgcn_s_sleep(4);
+          }
+          if (timed_out) {
+            if (lane == 0) *a.status = 1;
+            break;                                             // the id is not there: read nothing
+          }
+          have_id = true;
+          id = (int)(uint32_t)w2;
+        }
+        const int u = attend_unit(al, pd, p2, nv, pg, have_id, id);
         if (u >= 0) return make_int2(p2, u);
       }
       return make_int2(p_end, -1);
     };
-    if (phase == 1) {
-      // does this wave have a picked position at all?
-      bool mine = false;
-      for (int p2 = pos0; p2 < p_end; p2 += NW) mine = mine || (p2 >= pk_lo && p2 < pk_hi);
-      if (!mine) break;
-      // Wait for the block that makes this head's selection.  It is one of the scoring blocks of
-      // this launch, which all have lower block indices than any attention block and never wait
-      // for anything, so it is running or done; the wait is bounded all the same.  The whole wave
-      // polls the same word (one request per poll).
-      int it = 0;
-      while (__hip_atomic_load(a.sel_done + head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
-        if (++it > (1 << 16)) { timed_out = true; break; }   // ~0.1 s
-        __builtin_amdgcn_s_sleep(4);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // the id loads below stay behind the poll
-      if (timed_out) {
-        if (lane == 0) *a.status = 1;
-        break;                                                 // the ids are not there: read nothing
-      }
-    }
     // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
     // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
     int2 cur = find(pos0, n_valid, page);

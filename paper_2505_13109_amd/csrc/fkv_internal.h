@@ -80,7 +80,7 @@ int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t 
 // has to take the separate launches
 struct LayerIO {
   const int32_t* act_ids; float* part_o; float* part_ml; int max_splits; int* attn_counters; float* out;
-  int* sel_done; int epoch; int* status;
+  unsigned long long* tagged; int epoch; int* status;   // tagged: [heads][k] epoch-tagged copies of the picked ids
   int attn_epoch_bias;                       // 0; a test of the bounded wait makes attention wait for an epoch that never comes
   int* launch_grid; size_t* launch_lds;      // out (may be null): shape of the launch that was made
 };

@@ -217,7 +217,7 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     a.s.staged = lds_staged > lds_keys ? 1 : 0;
     a.s.fuse_select = 1;
     a.s.select_only = 0;
-    a.s.sel_done = lio.sel_done;
+    a.s.tagged = lio.tagged;
     a.s.epoch = lio.epoch;
     const int heads = d.batch * d.n_kv;
     const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
@@ -229,7 +229,7 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     at.counters = lio.attn_counters; at.out = lio.out; at.g = g;
     at.n_q = d.n_q; at.n_kv = d.n_kv; at.G = d.G; at.k = d.k; at.tstamp = io.tstamp;
     at.fused = 1; at.q_prev = io.q_prev; at.have_prev = io.have_prev; at.tau = io.tau; at.corr_pool = d.corr_pool;
-    at.k_new = io.k_new; at.v_new = io.v_new; at.sel_done = lio.sel_done; at.epoch = lio.epoch + lio.attn_epoch_bias; at.status = lio.status;
+    at.k_new = io.k_new; at.v_new = io.v_new; at.tagged = lio.tagged; at.epoch = lio.epoch + lio.attn_epoch_bias; at.status = lio.status;
     a.attn_block0 = grid;
     grid += heads * at.n_splits;
     const size_t lds_attn = (size_t)STEP_WAVES * (32 + d.G * D) * sizeof(float);

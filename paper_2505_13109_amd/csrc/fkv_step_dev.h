@@ -73,8 +73,8 @@ struct StepArgs {
   int fuse_select;           // the last scoring block of a head runs its selection (else: a second launch does)
   int select_only;           // this launch: one block per head, selection only
   long long* tstamp;         // debug: 100 MHz timestamps of head 0's phases (may be null)
-  int* sel_done;             // if not null: [heads], set to `epoch` once a head's page ids are out
-  int epoch;
+  unsigned long long* tagged; // if not null: [heads][k], every picked id once more as (epoch << 32 | id): a block of
+  int epoch;                  // this launch that waits for the selection polls the word it needs
 };
 
 // ---------------------------------------------------------------------------------
@@ -348,11 +348,17 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   int32_t* outu = a.ids_user ? a.ids_user + (size_t)head * k : nullptr;
   // No global store is issued before the last barrier of this function: a barrier waits for
   // the acknowledgement of every store the wave has in flight, a full trip to memory.
+  // a picked id goes out three ways: the layer's id list, the caller's copy, and (one-launch layer-step) tagged
+  // with the step's epoch in one 64-bit word, so that a waiting attention wave sees "this step's id" in one read
+  unsigned long long* tag = a.tagged ? a.tagged + (size_t)head * k : nullptr;
+  const unsigned long long tag_hi = (unsigned long long)(uint32_t)a.epoch << 32;
+  auto put_id = [&](int pos, int id) {
+    __hip_atomic_store(out + pos, id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tag) __hip_atomic_store(tag + pos, tag_hi | (uint32_t)id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (outu) outu[pos] = id;
+  };
   if (kk == 0) {
-    for (int i = tid; i < k; i += STEP_THREADS) {
-      __hip_atomic_store(out + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (outu) outu[i] = -1;
-    }
+    for (int i = tid; i < k; i += STEP_THREADS) put_id(i, -1);
     return;
   }
 #ifdef FKV_SEL_STAMPS
@@ -662,16 +668,12 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
     const uint32_t kj = key[j];
     if (kj > T || (kj == T && eq_before < take_eq)) {
       const uint32_t pos = gt_before + min(eq_before, take_eq);
-      __hip_atomic_store(out + pos, lo + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (outu) outu[pos] = lo + j;
+      put_id((int)pos, lo + j);
     }
     gt_before += (kj > T);
     eq_before += (kj == T);
   }
-  for (int i = kk + tid; i < k; i += STEP_THREADS) {   // padding
-    __hip_atomic_store(out + i, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (outu) outu[i] = -1;
-  }
+  for (int i = kk + tid; i < k; i += STEP_THREADS) put_id(i, -1);   // padding
 #ifdef FKV_SEL_STAMPS
   if (a.tstamp && head == 0 && tid == 0) {
     a.tstamp[40] = sel_t0; a.tstamp[41] = sel_t1; a.tstamp[42] = sel_t2; a.tstamp[43] = sel_t3;
@@ -709,7 +711,8 @@ __device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t*
     score_role<DT, G>(a, head, chunk);
     if (chunk == 0) FKV_STAMP(a, head, 1);
     if (!a.fuse_select) return;
-    if (!last_block_done(a.counters + head, a.blocks_per_head)) return;
+    if (a.blocks_per_head == 1) block_release();       // the head's only scoring block: its own weights, once they are out
+    else if (!last_block_done(a.counters + head, a.blocks_per_head)) return;
   }
   FKV_STAMP(a, head, 2);
   if (a.staged) select_block<G, true, ROOMY>(a, head, dyn_lds);
@@ -718,12 +721,7 @@ __device__ __forceinline__ void step_roles(const StepArgs& a, int bid, uint32_t*
 #ifdef FKV_SEL_STAMPS
   if (a.tstamp && threadIdx.x == 0) a.tstamp[24 + (head & 7)] = wall_clock64();
 #endif
-  if (a.sel_done) {
-    // the ids went out with device-scope stores; once every wave's have completed, announce them
-    block_release();
-    if (threadIdx.x == 0) __hip_atomic_store(a.sel_done + head, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  // the pooled scores, kept for inspection; after the announcement, which nothing here should delay
+  // the pooled scores, kept for inspection; after the ids, which nothing here should delay
   if (a.g.k_eff > 0)
     for (int j = threadIdx.x; j < a.g.n_cand; j += STEP_THREADS)
       a.score[(size_t)head * a.max_pages + a.g.cand_lo + j] = key_score(dyn_lds[j]);
