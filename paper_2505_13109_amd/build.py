@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfreekv.so")
-SOURCES = ["fkv_api.hip", "fkv_data.hip", "fkv_select.hip", "fkv_attn.hip"]
+SOURCES = ["fkv_api.hip", "fkv_data.hip", "fkv_select.hip", "fkv_attn.hip", "fkv_wide.hip"]
 
 # -ffp-contract=off: the arithmetic that decides page ids is written operation by operation.
 # packed fp32 ops are switched off for this target.

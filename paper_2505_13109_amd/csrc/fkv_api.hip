@@ -51,7 +51,7 @@ struct Layout {
   // per layer
   size_t pool, summ, qprev, ids, slots, flags, miss, cosine, counters, tagged, layer_bytes;
   // per context
-  size_t P, score, part_o, part_ml, dbg_page, tstamp, ctx_bytes;
+  size_t P, score, part_o, part_ml, dbg_page, tstamp, bmax, hmax, zsum, cand_key, cand_id, wide_cnt, ctx_bytes;
   size_t total;
   size_t host_layer_bytes, host_total;
   int units_per_head, ring_base, n_ring, sel_base, max_splits, k, max_pages;
@@ -86,6 +86,13 @@ Layout make_layout(const fkv_config& c) {
   l.part_ml = p; p += align_up((size_t)b * n_kv * l.max_splits * (n_q / n_kv) * 2 * 4);
   l.dbg_page = p; p += align_up((size_t)UNIT_BYTES);
   l.tstamp = p;  p += align_up((size_t)64 * 8);
+  // a selection spread over several blocks per head: per-head maxima and integer softmax sums, the slices' short lists
+  l.bmax = p;     p += align_up((size_t)b * n_kv * (l.max_pages / 32 + 1) * MAX_G * 4);   // one entry per scoring block of a head
+  l.hmax = p;     p += align_up((size_t)b * n_kv * MAX_G * 4);
+  l.zsum = p;     p += align_up((size_t)b * n_kv * MAX_G * 8);
+  l.cand_key = p; p += align_up((size_t)b * n_kv * WIDE_MAX_SLICES * (l.k > 0 ? l.k : 1) * 4);
+  l.cand_id = p;  p += align_up((size_t)b * n_kv * WIDE_MAX_SLICES * (l.k > 0 ? l.k : 1) * 4);
+  l.wide_cnt = p; p += align_up((size_t)b * n_kv * 4);
   l.ctx_bytes = p;
   l.total = l.layer_bytes * c.n_layers + l.ctx_bytes;
   l.host_layer_bytes = c.placement == FKV_PLACE_HOST ? (size_t)b * n_kv * l.max_pages * UNIT_BYTES : 0;
@@ -246,6 +253,14 @@ static StepIO make_step_io(fkv_ctx* ctx, int layer, const void* q, const void* k
   io.ids_user = ids_user;
   io.counters = ctx->sel_counters(layer);
   io.tstamp = ctx->tstamp();
+  char* cb = ctx->ctx_base();
+  io.bmax = reinterpret_cast<float*>(cb + ctx->lay.bmax);
+  io.bmax_stride = ctx->lay.max_pages / 32 + 1;
+  io.hmax = reinterpret_cast<float*>(cb + ctx->lay.hmax);
+  io.zsum = reinterpret_cast<unsigned long long*>(cb + ctx->lay.zsum);
+  io.cand_key = reinterpret_cast<uint32_t*>(cb + ctx->lay.cand_key);
+  io.cand_id = reinterpret_cast<int32_t*>(cb + ctx->lay.cand_id);
+  io.wide_counters = reinterpret_cast<int*>(cb + ctx->lay.wide_cnt);
   return io;
 }
 

@@ -74,7 +74,12 @@ struct StepIO {
   uint8_t* flags; uint8_t* flags_user; double* cosine;                               // correction test
   float* P; float* score; int32_t* ids; int32_t* ids_user; int* counters;            // selection
   long long* tstamp;                                                                 // debug timestamps or null
+  // scratch of a selection spread over several blocks per head (all may be null: then it is never spread)
+  float* bmax; int bmax_stride; float* hmax; unsigned long long* zsum; uint32_t* cand_key; int32_t* cand_id; int* wide_counters;
 };
+constexpr int WIDE_MAX_SLICES = 16;       // most blocks that share one head's selection
+bool wide_plan(const Dims& d, const Geom& g, int* B, int* slice);
+void launch_wide_select(const Dims& d, const StepIO& io, Geom g, int B, int slice, int n_score_blocks, hipStream_t st);
 int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t st);   // returns the launches made
 // the whole layer-step (step roles + attention) in one launch; false if this shape or placement
 // has to take the separate launches

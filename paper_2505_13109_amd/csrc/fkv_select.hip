@@ -55,8 +55,10 @@ static bool lds_fits_launch(size_t lds, int grid) {
   return lds * per_unit <= kLdsPerUnit;
 }
 
+struct WidePlan { const Dims* d; const StepIO* io; bool ok; int B, slice; };
+
 template <int DT, int G>
-static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st, const WidePlan& wp) {
   constexpr size_t kDefaultLimit = 64 * 1024 - 8 * 1024;   // minus this kernel's static LDS, rounded up
   const bool select = (a.roles & ROLE_SELECT) != 0;
   size_t lds = lds_staged;
@@ -71,7 +73,15 @@ static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, si
   // would hold the unit's slots for several memory round trips per block.
   a.fuse_select = (select && lds_fits_launch(lds, grid) && (g_fuse_mode < 0 ? grid <= kFuseMaxBlocks : g_fuse_mode == 1)) ? 1 : 0;
   a.select_only = 0;
+  // a long candidate list whose selection has its own launch anyway is spread over several blocks per head
+  const bool wide = wp.ok && select && !a.fuse_select;
+  a.bmax = wide ? wp.io->bmax : nullptr;
+  a.bmax_stride = wp.io->bmax_stride;
   step_kernel<DT, G><<<grid, STEP_THREADS, a.fuse_select ? lds : 0, st>>>(a);
+  if (wide) {
+    launch_wide_select(*wp.d, *wp.io, a.g, wp.B, wp.slice, a.blocks_per_head, st);
+    return 3;
+  }
   if (select && !a.fuse_select) {
     a.select_only = 1;
     step_kernel<DT, G><<<heads, STEP_THREADS, lds, st>>>(a);
@@ -81,9 +91,9 @@ static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, si
 }
 
 template <int DT>
-static int launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st) {
+static int launch_step_dt(StepArgs& a, int G, int grid, int heads, size_t lds_staged, size_t lds_keys, hipStream_t st, const WidePlan& wp) {
   switch (G) {
-#define FKV_CASE(GG) case GG: return launch_step_g<DT, GG>(a, grid, heads, lds_staged, lds_keys, st);
+#define FKV_CASE(GG) case GG: return launch_step_g<DT, GG>(a, grid, heads, lds_staged, lds_keys, st, wp);
     FKV_CASE(1) FKV_CASE(2) FKV_CASE(3) FKV_CASE(4) FKV_CASE(5) FKV_CASE(6) FKV_CASE(7) FKV_CASE(8)
 #undef FKV_CASE
     default: return 0;
@@ -155,8 +165,10 @@ int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t 
     while (chunks_per_block < 16 && blocks / chunks_per_block > 4 * kComputeUnits) chunks_per_block *= 2;
   }
   fill_step_args(d, roles, io, g, passes, false, a, grid, lds_staged, lds_keys, chunks_per_block);
-  if (d.dtype == 0) launches += launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
-  else              launches += launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st);
+  WidePlan wp{&d, &io, false, 0, 0};
+  wp.ok = (roles & ROLE_SELECT) && io.bmax && a.blocks_per_head <= io.bmax_stride && knob("FKV_NO_WIDE_SELECT", 0) == 0 && wide_plan(d, g, &wp.B, &wp.slice);
+  if (d.dtype == 0) launches += launch_step_dt<0>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st, wp);
+  else              launches += launch_step_dt<1>(a, d.G, grid, d.batch * d.n_kv, lds_staged, lds_keys, st, wp);
   return launches;
 }
 
@@ -207,6 +219,10 @@ static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t
 bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, hipStream_t st) {
   const int roles = ROLE_APPEND | ROLE_CORR | ROLE_SELECT;
   if (g_no_layer_kernel || io.pd.placement != 0 || d.k == 0 || append_races_selection(roles, g)) return false;
+  {   // a candidate list long enough for the selection to be spread over several blocks takes the separate launches
+    int wb, ws;
+    if (io.bmax && knob("FKV_NO_WIDE_SELECT", 0) == 0 && wide_plan(d, g, &wb, &ws)) return false;
+  }
   LayerArgs a{};
   int grid = 0;
   size_t lds = 0;

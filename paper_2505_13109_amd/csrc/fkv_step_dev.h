@@ -72,6 +72,8 @@ struct StepArgs {
   int staged;                // the G x n_cand weights fit in LDS next to the keys
   int fuse_select;           // the last scoring block of a head runs its selection (else: a second launch does)
   int select_only;           // this launch: one block per head, selection only
+  float* bmax;               // if not null: [heads][bmax_stride][MAX_G], every scoring block leaves the per-head maxima of
+  int bmax_stride;           // the weights it wrote (for a selection spread over several blocks per head)
   long long* tstamp;         // debug: 100 MHz timestamps of head 0's phases (may be null)
   unsigned long long* tagged; // if not null: [heads][k], every picked id once more as (epoch << 32 | id): a block of
   int epoch;                  // this launch that waits for the selection polls the word it needs
@@ -129,6 +131,16 @@ __device__ __forceinline__ void corr_role(const StepArgs& a, int head) {
   }
 }
 
+// Scores can be negative in the variants that pool the weights themselves: map the fp32 bit
+// pattern to an unsigned key with the same order (-0 counts as +0), and back.
+__device__ __forceinline__ uint32_t score_key(float sc) {
+  const uint32_t u = __float_as_uint(sc + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_score(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
 // ---------------------------------------------------------------------------------
 // role: page weights P^h_j from the min-max summaries (Sec. 3.2).
 // A 16-lane group owns one page: lane c8 holds channels 8*c8 .. 8*c8+7 of kmax and
@@ -180,6 +192,7 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
   }
   const float scale = 0x1.6a09e6p-4f;   // fl32(1/sqrt(128))
   float* const prow = a.P + (size_t)(b * a.n_q + m * G + (c8 < NG ? c8 : 0)) * a.max_pages;
+  float best = -__builtin_inff();                         // largest weight this lane has written (query head c8)
   // a block of a big scan takes every blocks_per_head-th chunk of its head, one after the other
   for (int ch = chunk; ch * pages_per_chunk < a.g.n_cand; ch += a.blocks_per_head) {
   if (ch != chunk) load_chunk(ch);
@@ -222,8 +235,24 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
     if (c8 < NG && page[ps] >= 0) {
       if (a.fuse_select) st_dev(prow + page[ps], mine * scale);
       else prow[page[ps]] = mine * scale;
+      best = fmaxf(best, mine * scale);
     }
   }
+  }
+  if (a.bmax) {
+    // the block's per-head maxima, for whoever needs the head's: over the wave's four 16-lane groups, then
+    // over the waves through LDS; plain stores (the readers are later launches)
+    __shared__ float s_best[STEP_WAVES][MAX_G];
+    best = fmaxf(best, __shfl_xor(best, 16, 64));
+    best = fmaxf(best, __shfl_xor(best, 32, 64));
+    if (lane < NG) s_best[wave][lane] = best;
+    __syncthreads();
+    if (threadIdx.x < NG) {
+      float v = s_best[0][threadIdx.x];
+#pragma unroll
+      for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_best[w][threadIdx.x]);
+      a.bmax[((size_t)head * a.bmax_stride + chunk) * MAX_G + threadIdx.x] = v;
+    }
   }
 }
 
@@ -252,16 +281,6 @@ __device__ __forceinline__ uint32_t softmax_fixed(float p, float mx) {
   float e31 = __builtin_ldexpf(r, (int)n + 31);
   if (t < -64.0f) e31 = 0.0f;
   return (uint32_t)__builtin_rintf(e31);
-}
-
-// Scores can be negative in the variants that pool the weights themselves: map the fp32 bit
-// pattern to an unsigned key with the same order (-0 counts as +0), and back.
-__device__ __forceinline__ uint32_t score_key(float sc) {
-  const uint32_t u = __float_as_uint(sc + 0.0f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float key_score(uint32_t key) {
-  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
 // A reciprocal of b good to an ulp or two: the hardware's approximation (a dozen bits would do)
@@ -312,6 +331,91 @@ __device__ __forceinline__ float pooled_score(const uint32_t* e, const double* z
     else if (mode == 3) acc = fmaxf(acc, __uint_as_float(e[gg]));
   }
   return mode == 2 ? (float)((double)acc / (double)G) : acc;
+}
+
+// ---------------------------------------------------------------------------------
+// Block-wide top-kk of n keys held in LDS, ties to the lower index: emit(pos, j) is called for the
+// chosen j in ascending order of j with pos = 0 .. kk-1 (whichever thread owns j calls it).
+// Before the call (and a barrier): hist[3] holds the counts of the keys' top bytes, hist[0..2] zeros.
+// 1 <= kk <= n.
+// ---------------------------------------------------------------------------------
+template <typename Emit>
+__device__ __forceinline__ void radix_topk(const uint32_t* key, int n, int kk, uint32_t (*hist)[256], uint32_t* s_scan,
+                                           Emit emit) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
+  // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
+  // It ends early once every key of the chosen bin is wanted: then "all keys from that bin
+  // upwards" is the answer and the lower bytes need not be resolved (every wave sees the same
+  // histogram, so the whole block takes the exit together).
+  uint32_t prefix = 0, remaining = (uint32_t)kk;
+  uint32_t T = 0, take_eq = 0;                       // take keys > T, and the first take_eq keys == T
+  bool resolved = false;
+#pragma unroll
+  for (int pass = 3; pass >= 0; --pass) {
+    if (resolved) continue;
+    const int shift = pass * 8;
+    if (pass != 3) {
+      for (int j = tid; j < n; j += STEP_THREADS) {
+        const uint32_t kj = key[j];
+        if ((kj >> (shift + 8)) == prefix) atomicAdd(&hist[pass][(kj >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+    }
+    uint32_t c[4], tot = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { c[i] = hist[pass][255 - 4 * lane - i]; tot += c[i]; }
+    const uint32_t incl = wave_scan_u32(tot);
+    uint32_t above = incl - tot;                     // keys in bins above this lane's
+    const bool mine = above < remaining && remaining <= incl;   // exactly one lane
+    uint32_t need = remaining - above;
+    int found = 0;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      if (found == i && c[i] < need) { need -= c[i]; found = i + 1; }
+    }
+    const unsigned long long pick = __ballot(mine);
+    const int src = __builtin_ctzll(pick);
+    const uint32_t cf = found == 0 ? c[0] : found == 1 ? c[1] : found == 2 ? c[2] : c[3];
+    remaining = (uint32_t)__builtin_amdgcn_readlane((int)need, src);          // how many to take inside the bin
+    const uint32_t in_bin = (uint32_t)__builtin_amdgcn_readlane((int)cf, src); // how many it holds
+    const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
+    prefix = (prefix << 8) | bin;
+    if (pass == 0) {
+      T = prefix;                                    // the kk-th largest key itself;
+      take_eq = remaining;                           // of the keys equal to it, the lowest ids
+      resolved = true;
+    } else if (remaining == in_bin && (prefix << shift) != 0) {
+      T = (prefix << shift) - 1;                     // everything from the bin's lowest key upwards
+      take_eq = 0;
+      resolved = true;
+    }
+  }
+
+  // ordered compaction: thread t owns the contiguous ids [t*per, (t+1)*per)
+  const int per = (n + STEP_THREADS - 1) / STEP_THREADS;
+  const int j0 = tid * per, j1 = min(n, j0 + per);
+  uint32_t cnt = 0;                                  // low 16 bits: keys > T, high 16 bits: keys == T
+  for (int j = j0; j < j1; ++j) {
+    const uint32_t kj = key[j];
+    cnt += (kj > T ? 1u : 0u) + (kj == T ? 0x10000u : 0u);
+  }
+  const uint32_t incl = wave_scan_u32(cnt);
+  if (lane == 63) s_scan[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += s_scan[w];
+  const uint32_t excl = base + incl - cnt;
+  uint32_t gt_before = excl & 0xffffu, eq_before = excl >> 16;
+  for (int j = j0; j < j1; ++j) {
+    const uint32_t kj = key[j];
+    if (kj > T || (kj == T && eq_before < take_eq)) {
+      const uint32_t pos = gt_before + min(eq_before, take_eq);
+      emit((int)pos, j);
+    }
+    gt_before += (kj > T);
+    eq_before += (kj == T);
+  }
 }
 
 // Most candidates of a KV head the selection keeps in registers (G values each).  The layer kernel
@@ -599,80 +703,8 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   __syncthreads();
 
   FKV_SEL_MARK(3);
-  // radix select: the kk-th largest key, one byte at a time from the top.  Every wave scans
-  // the histogram itself (lane l owns bins 255-4l .. 252-4l), so a pass costs one barrier.
-  // It ends early once every key of the chosen bin is wanted: then "all keys from that bin
-  // upwards" is the answer and the lower bytes need not be resolved (every wave sees the same
-  // histogram, so the whole block takes the exit together).
-  uint32_t prefix = 0, remaining = (uint32_t)kk;
-  uint32_t T = 0, take_eq = 0;                       // take keys > T, and the first take_eq keys == T
-  bool resolved = false;
-#pragma unroll
-  for (int pass = 3; pass >= 0; --pass) {
-    if (resolved) continue;
-    const int shift = pass * 8;
-    if (pass != 3) {
-      for (int j = tid; j < n; j += STEP_THREADS) {
-        const uint32_t kj = key[j];
-        if ((kj >> (shift + 8)) == prefix) atomicAdd(&hist[pass][(kj >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-    }
-    uint32_t c[4], tot = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { c[i] = hist[pass][255 - 4 * lane - i]; tot += c[i]; }
-    const uint32_t incl = wave_scan_u32(tot);
-    uint32_t above = incl - tot;                     // keys in bins above this lane's
-    const bool mine = above < remaining && remaining <= incl;   // exactly one lane
-    uint32_t need = remaining - above;
-    int found = 0;
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      if (found == i && c[i] < need) { need -= c[i]; found = i + 1; }
-    }
-    const unsigned long long pick = __ballot(mine);
-    const int src = __builtin_ctzll(pick);
-    const uint32_t cf = found == 0 ? c[0] : found == 1 ? c[1] : found == 2 ? c[2] : c[3];
-    remaining = (uint32_t)__builtin_amdgcn_readlane((int)need, src);          // how many to take inside the bin
-    const uint32_t in_bin = (uint32_t)__builtin_amdgcn_readlane((int)cf, src); // how many it holds
-    const uint32_t bin = (uint32_t)__builtin_amdgcn_readlane(255 - 4 * lane - found, src);
-    prefix = (prefix << 8) | bin;
-    if (pass == 0) {
-      T = prefix;                                    // the kk-th largest key itself;
-      take_eq = remaining;                           // of the keys equal to it, the lowest ids
-      resolved = true;
-    } else if (remaining == in_bin && (prefix << shift) != 0) {
-      T = (prefix << shift) - 1;                     // everything from the bin's lowest key upwards
-      take_eq = 0;
-      resolved = true;
-    }
-  }
+  radix_topk(key, n, kk, hist, s_scan, [&](int pos, int j) { put_id(pos, lo + j); });
   FKV_SEL_MARK(4);
-
-  // ordered compaction: thread t owns the contiguous ids [t*per, (t+1)*per)
-  const int per = (n + STEP_THREADS - 1) / STEP_THREADS;
-  const int j0 = tid * per, j1 = min(n, j0 + per);
-  uint32_t cnt = 0;                                  // low 16 bits: keys > T, high 16 bits: keys == T
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t kj = key[j];
-    cnt += (kj > T ? 1u : 0u) + (kj == T ? 0x10000u : 0u);
-  }
-  const uint32_t incl = wave_scan_u32(cnt);
-  if (lane == 63) s_scan[wave] = incl;
-  __syncthreads();
-  uint32_t base = 0;
-  for (int w = 0; w < wave; ++w) base += s_scan[w];
-  const uint32_t excl = base + incl - cnt;
-  uint32_t gt_before = excl & 0xffffu, eq_before = excl >> 16;
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t kj = key[j];
-    if (kj > T || (kj == T && eq_before < take_eq)) {
-      const uint32_t pos = gt_before + min(eq_before, take_eq);
-      put_id((int)pos, lo + j);
-    }
-    gt_before += (kj > T);
-    eq_before += (kj == T);
-  }
   for (int i = kk + tid; i < k; i += STEP_THREADS) put_id(i, -1);   // padding
 #ifdef FKV_SEL_STAMPS
   if (a.tstamp && head == 0 && tid == 0) {

@@ -697,6 +697,8 @@ def test_selection_paths_of_the_separate_step_kernel():
         (3, 2, 1, 50000),     # 1558 candidates, G <= 4: in registers, 4 per thread
         (4, 2, 2, 90000),     # 2808 candidates: staged in LDS, selection in its own launch
         (6, 2, 3, 20000),     # 621 candidates: 2 per thread
+        (4, 2, 1, 200000),    # 6246 candidates: the selection of a head spread over 13 blocks (maxima, sums, short lists, merge)
+        (7, 1, 2, 170000),    # 5308 candidates, G = 7, two requests: 11 blocks per head
     ]
     for i, (G, n_kv, batch, ctx) in enumerate(shapes):
         wl = W.Workload(f"sel{i}", 1, batch, G * n_kv, n_kv, "bf16", ctx, 1024, 64, 64, 0.8, 5, 0.8, 0.6, 400 + i, placement=1)
