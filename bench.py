@@ -33,6 +33,11 @@ HBM_PEAK_GBPS = 8000.0
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs scaled by a copy kernel of known
 # size (profiles/layer_step_c2_pmc.txt).  None until measured.
 MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9396100, "layer_kernel": 14027600}
+TRAFFIC_SOURCE = ("profiles/layer_step_c2_pmc.txt: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE over this command with "
+                  "--calibration-copy, KiB per dispatch scaled by what the same counters read for a 256 MiB copy")
+# the same for the two kernels of the batch-32 shape (profiles/decode_step_c2_batch32_kernels_and_pmc.txt)
+MEASURED_TRAFFIC_BYTES_B32 = {"attn_kernel": 273586000, "step_kernel": 137420000}
+TRAFFIC_SOURCE_B32 = "profiles/decode_step_c2_batch32_kernels_and_pmc.txt (same method, batch-32 shape)"
 
 
 def algorithmic_bytes(wl):
@@ -99,12 +104,25 @@ def saturated_rate(torch, fkv, wl, batch, layers=2, steps=16, warmup=4):
     torch.cuda.synchronize()
     us = (time.perf_counter() - t_begin) / (steps * layers) * 1e6
     attn_ms, attn_n = ctx.profile_attn(q[n_steps - 1], out[0], 4, stream=stream)
+    sel_ms, sel_n = ctx.profile_select(q[n_steps - 1], 4, stream=stream)
     for layer in range(layers):
         ctx.health(layer)
     launches = ctx.step_launches(0)
     ctx.close()
     score_b, attn_b = algorithmic_bytes(ws)
-    return {"batch": batch, "layers": layers, "steps": steps, "launches_per_layer_step": launches,
+    attn_s, scan_s = attn_ms / attn_n * 1e-3, sel_ms / (4 * layers) * 1e-3
+    # the two HBM readers of this shape, each timed back to back on its own between one HIP event pair on the launch
+    # stream; the scan's time includes the selection launch that follows it (one block per KV head, no HBM stream)
+    roof = [{"bound": "hbm", "kernel": "attn_kernel (split sparse decode attention)", "achieved": attn_b / attn_s / 1e9,
+             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": attn_b / attn_s / 1e9 / HBM_PEAK_GBPS,
+             "traffic": MEASURED_TRAFFIC_BYTES_B32["attn_kernel"] if batch == 32 and wl.name == "c2" else None,
+             "traffic_source": TRAFFIC_SOURCE_B32, "algorithmic_bytes_per_launch": attn_b, "avg_launch_us": attn_s * 1e6},
+            {"bound": "hbm", "kernel": "step_kernel (page-weight scan over the min-max summaries) + the selection launch behind it",
+             "achieved": score_b / scan_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": score_b / scan_s / 1e9 / HBM_PEAK_GBPS,
+             "traffic": MEASURED_TRAFFIC_BYTES_B32["step_kernel"] if batch == 32 and wl.name == "c2" else None,
+             "traffic_source": TRAFFIC_SOURCE_B32, "algorithmic_bytes_per_launch": score_b,
+             "avg_launch_us": scan_s * 1e6, "launches_per_scan": sel_n // (4 * layers)}]
+    return {"roofline": roof, "batch": batch, "layers": layers, "steps": steps, "launches_per_layer_step": launches,
             "us_per_layer_step": us, "algorithmic_MB_per_layer_step": (score_b + attn_b) / 1e6,
             "path_algorithmic_GBps": (score_b + attn_b) / us / 1e3,
             "path_frac_of_hbm_peak": (score_b + attn_b) / us / 1e3 / HBM_PEAK_GBPS,
@@ -429,6 +447,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES["layer_kernel" if one_launch else "attn_kernel"] if wl.name == "c2" else None,
+                     "traffic_source": TRAFFIC_SOURCE if wl.name == "c2" else None,
                      "algorithmic_bytes_per_launch": kern_b, "avg_launch_us": kern_s * 1e6,
                      "launches_timed": kern_n,
                      "standalone_attn_kernel_us": attn_ms / max(attn_n, 1) * 1e3,
@@ -441,7 +460,9 @@ def main():
     torch.cuda.empty_cache()
     if args.saturation_batch > 0 and wl.name == "c2" and args.batch == 0 and not args.real_layer and not args.standin_mb:
         try:                             # a side measurement: it must not cost the line above
-            res["config"]["saturated_shape"] = saturated_rate(torch, fkv, wl, args.saturation_batch)
+            sat = saturated_rate(torch, fkv, wl, args.saturation_batch)
+            res["roofline_saturated_shape"] = sat.pop("roofline")
+            res["config"]["saturated_shape"] = sat
         except Exception as e:           # noqa: BLE001
             res["config"]["saturated_shape"] = {"error": f"{type(e).__name__}: {e}"}
     if cpu is not None:

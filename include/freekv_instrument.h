@@ -28,6 +28,13 @@ int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches);
 int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, float* out_dev, int32_t reps,
                      void* stream, double* total_ms, int32_t* launches);
 
+/* The same for the page-weight scan and the selection (Sec. 3.2) as fkv_page_select launches them: `reps`
+ * times for every layer in turn between one HIP event pair; `launches` receives the kernel launches made
+ * (one per call when the selection rides in the scoring launch, more otherwise).  The layers' PENDING id
+ * buffers are overwritten; no other state changes.  Blocking. */
+int fkv_profile_select(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, int32_t reps, void* stream,
+                       double* total_ms, int32_t* launches);
+
 /* The cost of a launch as such: `reps` launches, back to back on `stream` between one HIP event
  * pair, of a kernel with the grid, block size and dynamic LDS of `layer`'s last one-launch
  * layer-step whose blocks return at once.  FKV_ESTATE if that step took several launches.

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len", "fkv_health",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
+    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_select", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
     "fkv_sparse_decode_attn_static", "fkv_recall_pending", "fkv_attach_nhd_pool", "fkv_test_lose_selection", "fkv_instrument_timestamps",
 )
 
@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
         "fkv_profile_enable": (C.c_int, [vp, i32]),
         "fkv_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "fkv_profile_attn": (C.c_int, [vp, vp, sz, vp, i32, vp, C.POINTER(C.c_double), C.POINTER(i32)]),
+        "fkv_profile_select": (C.c_int, [vp, vp, sz, i32, vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "fkv_profile_launch_floor": (C.c_int, [vp, i32, i32, vp, C.POINTER(C.c_double), C.POINTER(i32), C.POINTER(i32)]),
         "fkv_debug_read": (C.c_int, [vp, i32, i32, vp, sz]),
         "fkv_debug_read_page": (C.c_int, [vp, i32, i32, i32, i32, i32, vp]),
@@ -249,6 +250,14 @@ class FreeKV:
         stride = q_layers.stride(0) * q_layers.element_size()
         self._check(self.L.fkv_profile_attn(self._h, _ptr(q_layers), stride, _ptr(out), reps, _stream(stream),
                                             C.byref(ms), C.byref(n)), "fkv_profile_attn")
+        return ms.value, n.value
+
+    def profile_select(self, q_layers, reps, stream=None):
+        """q_layers: [n_layers, batch, n_q, d] contiguous; returns (total_ms, launches) of scan + selection."""
+        ms, n = C.c_double(), C.c_int32()
+        stride = q_layers.stride(0) * q_layers.element_size()
+        self._check(self.L.fkv_profile_select(self._h, _ptr(q_layers), stride, reps, _stream(stream),
+                                              C.byref(ms), C.byref(n)), "fkv_profile_select")
         return ms.value, n.value
 
     def health(self, layer):

@@ -858,6 +858,37 @@ int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, flo
   return FKV_OK;
 }
 
+int fkv_profile_select(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, int32_t reps, void* stream,
+                       double* total_ms, int32_t* launches) {
+  if (!ctx || !q_dev || !total_ms || !launches || reps < 1) return FKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int l = 0; l < ctx->cfg.n_layers; ++l)
+    if (ctx->layers[l].L < 1) return ctx->fail(FKV_ESTATE, "every layer needs a context");
+  hipEvent_t e0, e1;
+  FKV_HIP(ctx, hipEventCreate(&e0));
+  FKV_HIP(ctx, hipEventCreate(&e1));
+  FKV_HIP(ctx, hipDeviceSynchronize());
+  FKV_HIP(ctx, hipEventRecord(e0, st));
+  int n = 0;
+  for (int r = 0; r < reps; ++r) {
+    for (int l = 0; l < ctx->cfg.n_layers; ++l) {
+      const StepIO io = make_step_io(ctx, l, static_cast<const char*>(q_dev) + q_layer_stride * l, nullptr, nullptr, nullptr, nullptr);
+      n += launch_step(ctx->dims, ROLE_SELECT, io, make_geom(ctx->cfg, ctx->layers[l].L), st);
+    }
+  }
+  FKV_HIP(ctx, hipEventRecord(e1, st));
+  FKV_HIP(ctx, hipEventSynchronize(e1));
+  float ms = 0.f;
+  FKV_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  int rc = after_launch(ctx, "step kernels");
+  if (rc) return rc;
+  *total_ms = ms;
+  *launches = n;
+  return FKV_OK;
+}
+
 int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* stream, double* total_ms,
                              int32_t* grid, int32_t* lds_bytes) {
   FKV_CHECK_LAYER(ctx, layer);
