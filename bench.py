@@ -370,7 +370,8 @@ def main():
     extra = {}
     floor = {}
     if one_launch:
-        # what a launch of that shape costs when its blocks return at once
+        # what a launch of that shape costs when its blocks return at once, and the roofline fraction of the time
+        # that is left when that cost is taken out (the launch cost is paid whatever the kernel does)
         f_ms, f_grid, f_lds = ctx.profile_launch_floor(0, 2048, stream=stream)
         floor = {"empty_launch_same_shape_us": f_ms / 2048 * 1e3, "grid_blocks": f_grid, "dynamic_lds_bytes": f_lds}
     if wl.placement == 1:
@@ -451,7 +452,9 @@ def main():
                      "algorithmic_bytes_per_launch": kern_b, "avg_launch_us": kern_s * 1e6,
                      "launches_timed": kern_n,
                      "standalone_attn_kernel_us": attn_ms / max(attn_n, 1) * 1e3,
-                     "event_pair_per_launch_us": pair_ms / max(pair_n, 1) * 1e3, **floor},
+                     "event_pair_per_launch_us": pair_ms / max(pair_n, 1) * 1e3, **floor,
+                     **({"frac_of_peak_with_the_empty_launch_taken_out":
+                         kern_b / max(kern_s - floor["empty_launch_same_shape_us"] * 1e-6, 1e-9) / 1e9 / HBM_PEAK_GBPS} if floor else {})},
     }
     for layer in range(wl.n_layers):
         ctx.health(layer)                # no kernel gave up a bounded wait

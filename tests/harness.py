@@ -78,30 +78,6 @@ class Pair:
         vb = np.stack([self.vd[(li, r)][1][t] for r in range(wl.batch)])
         return to_dev(qb, wl.dtype), to_dev(kb, wl.dtype), to_dev(vb, wl.dtype)
 
-    def step_hip_only(self, li, t):
-        """Advance the HIP side alone by decode step t; `resync_oracle` brings the oracle back in step."""
-        q, k, v = self.step_inputs(li, t)
-        self.g.decode_step(li, q, k, v, self.out, copy_stream=self.copy_stream)
-
-    def resync_oracle(self, li, t0):
-        """Put the oracles of layer index li into the state they have before decode step t0 without
-        walking there.  That state is a function of the inputs alone: the tokens so far (bulk-loaded
-        summaries equal incremental ones), q_{t0-1}, and the pages Sel(q_{t0-1}) picked at step t0-1,
-        which every head has committed by the end of that step (Sec. 3.3) -- so one oracle step from
-        a fresh load reproduces it."""
-        assert t0 >= 1
-        wl = self.wl
-        for r in range(wl.batch):
-            (K, _), (V, _) = W.kv_prefix(wl, self.layers[li], r, self.n_ctx)
-            kd, vd = self.kd[(li, r)][0], self.vd[(li, r)][0]
-            old = self.oracles[(li, r)]
-            o = O.FreeKVOracle(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.page_size, wl.budget, wl.sink,
-                               wl.window, self.tau, self.max_ctx,
-                               select_pooling=old.select_pooling, corr_pooling=old.corr_pooling)
-            o.load_prefix_bulk(np.concatenate([K, kd[:t0 - 1]]), np.concatenate([V, vd[:t0 - 1]]))
-            o.step(self.q[(li, r)][0][t0 - 1], kd[t0 - 1], vd[t0 - 1])
-            self.oracles[(li, r)] = o
-
     def check_summaries(self, li):
         wl = self.wl
         s = W.decode(self.g.debug_read(li, B.DBG_SUMMARIES), wl.dtype)
