@@ -42,10 +42,10 @@ int fkv_profile_select(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, i
 int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* stream, double* total_ms,
                              int32_t* grid, int32_t* lds_bytes);
 
-/* Test hook for the bounded wait of the one-launch layer-step: while on, the attention blocks of a
- * corrected head wait for an announcement of their head's selection that never comes (the host asks
- * them to wait for the wrong epoch).  Every kernel still ends; the wait runs out after about 0.1 s, the
- * head's output rows are NaN and fkv_health reports FKV_ETIMEOUT.  Host-side switch, no GPU work. */
+/* Test hook for the bounded wait of the one-launch layer-step: while on, the attention waves of a
+ * corrected head wait for picked page ids tagged with an epoch that never comes (the host asks them to
+ * wait for the wrong one).  Every kernel still ends; the wait runs out after about 0.1 s, the head's
+ * output rows are NaN and fkv_health reports FKV_ETIMEOUT.  Host-side switch, no GPU work. */
 int fkv_test_lose_selection(fkv_ctx* ctx, int32_t on);
 
 /* While on, kernels record 100 MHz phase timestamps of head 0 (read with FKV_DBG_TSTAMP). */

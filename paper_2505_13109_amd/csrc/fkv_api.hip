@@ -76,7 +76,7 @@ Layout make_layout(const fkv_config& c) {
   l.flags = o;  o += align_up((size_t)b * n_kv);
   l.miss = o;   o += align_up((size_t)b * n_kv * (1 + 3 * l.k) * 4);   // per head: count, page ids, slots, positions in the picked list
   l.cosine = o; o += align_up((size_t)b * n_q * 8);
-  l.counters = o; o += align_up((size_t)(3 * b * n_kv + 1) * 4);   // last-block counters (selection, attention), selection epochs, status
+  l.counters = o; o += align_up((size_t)(2 * b * n_kv + 1) * 4);   // last-block counters (selection, attention), then the status word
   l.tagged = o; o += align_up((size_t)b * n_kv * (l.k > 0 ? l.k : 1) * 8);   // epoch-tagged copies of the picked ids (one-launch layer-step)
   l.layer_bytes = o;
   size_t p = 0;
@@ -182,7 +182,7 @@ struct fkv_ctx {
   int* sel_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters); }
   int* attn_counters(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + cfg.batch * cfg.n_kv_heads; }
   unsigned long long* tagged(int l) const { return reinterpret_cast<unsigned long long*>(layer_base(l) + lay.tagged); }
-  int* status(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + 3 * cfg.batch * cfg.n_kv_heads; }
+  int* status(int l) const { return reinterpret_cast<int*>(layer_base(l) + lay.counters) + 2 * cfg.batch * cfg.n_kv_heads; }
   float* P() const { return reinterpret_cast<float*>(ctx_base() + lay.P); }
   float* score() const { return reinterpret_cast<float*>(ctx_base() + lay.score); }
   float* part_o() const { return reinterpret_cast<float*>(ctx_base() + lay.part_o); }

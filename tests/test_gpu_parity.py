@@ -552,7 +552,7 @@ def test_streamed_recall_into_an_nhd_pool():
 
 def test_a_wait_that_runs_out_is_reported():
     """The bounded wait of a corrected head's attention: with the library's test hook on, the waves that
-    attend picked pages wait for an announcement that never comes.  Every kernel still ends; the failure
+    attend picked pages wait for ids of an epoch that never comes.  Every kernel still ends; the failure
     shows on the data path (the outputs of the query groups are NaN) and fkv_health reports it once.
     With the hook off again the same context decodes normally."""
     import paper_2505_13109_amd as fkv
