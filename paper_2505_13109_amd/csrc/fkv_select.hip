@@ -19,6 +19,28 @@ __global__ __launch_bounds__(STEP_THREADS, STEP_THREADS <= 256 ? 2 : 1) void ste
   step_roles<DT, G, false>(a, blockIdx.x, dyn_lds);
 }
 
+// The scan of the bandwidth-bound regime: append, correction test and page weights only (the selection has
+// a launch of its own there), in 256-thread blocks of one 64-page chunk each.  Measured on the scan alone
+// (256 heads x 992 pages, 130 MB; a plain read of the same bytes takes 22.1 us = 5.9 TB/s on this machine):
+// 23.9 us in this shape against 25.7 us with 512-thread blocks of 128 pages -- the smaller block leaves
+// the unit's slots in finer pieces, so that more blocks are in different phases (loading, computing,
+// draining) at any time; blocks that take several chunks, pipelined or not, are slower than either.
+constexpr int SCAN_WAVES = 4, SCAN_PASSES = 4;
+template <int DT, int G>
+__global__ __launch_bounds__(SCAN_WAVES * 64) void scan_kernel(StepArgs a) {
+  const int heads = a.batch * a.n_kv;
+  int bid = blockIdx.x;
+  if (a.roles & ROLE_APPEND) {
+    if (bid < heads) { append_role<DT>(a, bid); return; }
+    bid -= heads;
+  }
+  if (a.roles & ROLE_CORR) {
+    if (bid < heads) { corr_role<DT, G, SCAN_WAVES>(a, bid); return; }
+    bid -= heads;
+  }
+  score_role<DT, G, SCAN_WAVES>(a, bid / a.blocks_per_head, bid % a.blocks_per_head);
+}
+
 // Dynamic LDS above the default 64 KiB per block has to be granted per kernel function.
 // Returns false if the device refuses (the caller then keeps only the keys in LDS).
 template <int DT, int G>
@@ -47,6 +69,7 @@ constexpr int kLayerMaxBlocks = 4 * kComputeUnits;  // shapes up to this size ta
 static const int g_chunks_per_block = knob("FKV_SCORE_CHUNKS", 0);
 static const int g_fuse_mode = knob("FKV_FUSE_SELECT", -1);
 static const int g_min_passes = knob("FKV_LAYER_PASSES", 0);
+static const bool g_scan_kernel = knob("FKV_NO_SCAN_KERNEL", 0) == 0;   // 1: scans stay in 512-thread step_kernel blocks
 // may every block of a `grid`-block launch carry `lds` bytes without starving the scoring blocks?
 static bool lds_fits_launch(size_t lds, int grid) {
   int per_unit = (grid + kComputeUnits - 1) / kComputeUnits;   // blocks a unit should hold at once
@@ -77,6 +100,26 @@ static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, si
   const bool wide = wp.ok && select && !a.fuse_select;
   a.bmax = wide ? wp.io->bmax : nullptr;
   a.bmax_stride = wp.io->bmax_stride;
+  if (select && !a.fuse_select && g_scan_kernel) {
+    // the selection does not ride along: the roles go to the scan kernel, one 64-page chunk per 256-thread block
+    StepArgs sa = a;
+    sa.passes = SCAN_PASSES;
+    sa.blocks_per_head = a.g.n_cand > 0 ? (a.g.n_cand + SCAN_WAVES * 4 * SCAN_PASSES - 1) / (SCAN_WAVES * 4 * SCAN_PASSES) : 1;
+    int sgrid = heads * sa.blocks_per_head;
+    if (sa.roles & ROLE_APPEND) sgrid += heads;
+    if (sa.roles & ROLE_CORR) sgrid += heads;
+    const bool fits = !wide || sa.blocks_per_head <= sa.bmax_stride;
+    if (fits) {
+      scan_kernel<DT, G><<<sgrid, SCAN_WAVES * 64, 0, st>>>(sa);
+      if (wide) {
+        launch_wide_select(*wp.d, *wp.io, a.g, wp.B, wp.slice, sa.blocks_per_head, st);
+        return 3;
+      }
+      a.select_only = 1;
+      step_kernel<DT, G><<<heads, STEP_THREADS, lds, st>>>(a);
+      return 2;
+    }
+  }
   step_kernel<DT, G><<<grid, STEP_THREADS, a.fuse_select ? lds : 0, st>>>(a);
   if (wide) {
     launch_wide_select(*wp.d, *wp.io, a.g, wp.B, wp.slice, a.blocks_per_head, st);

@@ -105,12 +105,12 @@ __device__ __forceinline__ void append_role(const StepArgs& a, int head) {
 // ---------------------------------------------------------------------------------
 // role: correction test (Sec. 3.1, 3.3).  One wave per query head, fp64.
 // ---------------------------------------------------------------------------------
-template <int DT, int G>
+template <int DT, int G, int WAVES = STEP_WAVES>
 __device__ __forceinline__ void corr_role(const StepArgs& a, int head) {
   __shared__ double cg[MAX_G];
   const int b = head / a.n_kv, m = head % a.n_kv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int gg = wave; gg < G; gg += STEP_WAVES) {
+  for (int gg = wave; gg < G; gg += WAVES) {
     const size_t off = (size_t)(b * a.n_q + m * G + gg) * D;
     double cosv = 0.0;
     uint32_t qw;
@@ -147,8 +147,9 @@ __device__ __forceinline__ float key_score(uint32_t key) {
 // kmin (one 16-byte load each, 1 KiB contiguous per wave and array), so a wave
 // scores 4 pages and a block 16 pages.
 // ---------------------------------------------------------------------------------
-template <int DT, int G, bool QMODE>
+template <int DT, int G, bool QMODE, int WAVES = STEP_WAVES>
 __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chunk) {
+  constexpr int PAGES_PER_PASS = WAVES * 4;               // (of this block size)
   const int b = head / a.n_kv, m = head % a.n_kv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane >> 4, c8 = lane & 15;
@@ -242,7 +243,7 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
   if (a.bmax) {
     // the block's per-head maxima, for whoever needs the head's: over the wave's four 16-lane groups, then
     // over the waves through LDS; plain stores (the readers are later launches)
-    __shared__ float s_best[STEP_WAVES][MAX_G];
+    __shared__ float s_best[WAVES][MAX_G];
     best = fmaxf(best, __shfl_xor(best, 16, 64));
     best = fmaxf(best, __shfl_xor(best, 32, 64));
     if (lane < NG) s_best[wave][lane] = best;
@@ -250,16 +251,16 @@ __device__ __forceinline__ void score_pages(const StepArgs& a, int head, int chu
     if (threadIdx.x < NG) {
       float v = s_best[0][threadIdx.x];
 #pragma unroll
-      for (int w = 1; w < STEP_WAVES; ++w) v = fmaxf(v, s_best[w][threadIdx.x]);
+      for (int w = 1; w < WAVES; ++w) v = fmaxf(v, s_best[w][threadIdx.x]);
       a.bmax[((size_t)head * a.bmax_stride + chunk) * MAX_G + threadIdx.x] = v;
     }
   }
 }
 
-template <int DT, int G>
+template <int DT, int G, int WAVES = STEP_WAVES>
 __device__ __forceinline__ void score_role(const StepArgs& a, int head, int chunk) {
-  if (a.sel_pool >= 4) score_pages<DT, G, true>(a, head, chunk);
-  else                 score_pages<DT, G, false>(a, head, chunk);
+  if (a.sel_pool >= 4) score_pages<DT, G, true, WAVES>(a, head, chunk);
+  else                 score_pages<DT, G, false, WAVES>(a, head, chunk);
 }
 
 // ---------------------------------------------------------------------------------
