@@ -179,6 +179,7 @@ def main():
     ap.add_argument("--placement", type=int, default=-1, help="override KV placement: 0 HBM, 1 pinned host pool")
     ap.add_argument("--batch", type=int, default=0, help="override the number of requests (stated in config.workload)")
     ap.add_argument("--tau", type=float, default=None, help="override the correction threshold (stated in config.workload)")
+    ap.add_argument("--rho", type=float, default=None, help="override the adjacent-step query correlation (stated in config.workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--standin-mb", type=int, default=0,
                     help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
@@ -214,6 +215,8 @@ def main():
         wl = wl.scaled(tau=args.tau)
     if args.batch > 0:
         wl = wl.scaled(batch=args.batch)
+    if args.rho is not None:
+        wl = wl.scaled(rho=args.rho, q_noise=math.sqrt(max(0.0, 1.0 - args.rho * args.rho)))
     # the CPU baseline first: its workers are forked, which has to happen before the GPU is initialised
     cpu = None
     if not args.no_cpu_baseline:
@@ -317,6 +320,7 @@ def main():
             t0 = t1
             print(f"bench.py: {t0 - Wm} of {K} timed steps enqueued, {time.perf_counter() - t_begin:.0f} s", file=sys.stderr, flush=True)
     ev1.record(stream)
+    t_enqueued = time.perf_counter() - t_begin     # the host is done submitting; the GPU may still be working
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
     region_ms = ev0.elapsed_time(ev1)
@@ -439,6 +443,7 @@ def main():
                                f"KV {'in HBM' if wl.placement == 0 else 'in pinned host memory'}",
                    "layer_steps_per_step": wl.n_layers,
                    "us_per_layer_step": elapsed / layer_steps * 1e6,
+                   "host_submit_us_per_layer_step": t_enqueued / layer_steps * 1e6,
                    "path_algorithmic_GBps": (score_b + attn_b) * layer_steps / elapsed / 1e9,
                    **({"standin_MB_per_layer_step": args.standin_mb} if args.standin_mb else {}),
                    **({"real_layer": "QKV + RoPE + o_proj + SwiGLU FFN GEMVs with random weights around every layer-step "

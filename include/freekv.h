@@ -131,7 +131,9 @@ int fkv_context_len(const fkv_ctx* ctx, int32_t layer);
 int fkv_health(fkv_ctx* ctx, int32_t layer);
 
 /* Kernel launches the last fkv_decode_step of `layer` put on the compute stream: 1 when the
- * whole layer-step ran as one launch (KV in HBM, selection small enough), more otherwise. */
+ * whole layer-step ran as one launch (selection small enough; with the KV in a host pool also:
+ * recall by the gather kernel into the library's own page cache), more otherwise.  The deferred
+ * recall on the copy stream is not counted. */
 int fkv_step_launches(const fkv_ctx* ctx, int32_t layer);
 
 /* ---- data plane ------------------------------------------------------- */
@@ -259,9 +261,18 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer);
  * append -> correction test -> selection for all heads -> recall for corrected
  * heads -> attention (corrected heads on the new pages, others on the reused
  * ones) -> deferred recall for the other heads on copy_stream -> commit.
- * No host synchronisation.  copy_stream may equal compute_stream. */
+ * No host synchronisation.  copy_stream may equal compute_stream.
+ * When the layer-step runs as one launch with the KV in a host pool, the deferred recall is not
+ * put on copy_stream at once: up to 8 layers' recalls are submitted together (one dependency
+ * between the two streams instead of one per layer) -- with the 8th such layer, with the last
+ * layer of the context, with the same layer's next step, and by any other call on the context.
+ * A caller that wants them on copy_stream now (to synchronise that stream itself) calls fkv_flush. */
 int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev,
                     const void* v_new_dev, float* out_dev, void* compute_stream, void* copy_stream);
+
+/* Submits every deferred recall (Sec. 3.2) that fkv_decode_step has kept back, on the streams of the
+ * steps that made them.  Nothing to do is not an error.  Only enqueues. */
+int fkv_flush(fkv_ctx* ctx);
 
 /* ---- introspection for tests (blocking: synchronises the device) --------- */
 #define FKV_DBG_SUMMARIES   0  /* T     [batch, n_kv, 2 (max,min), max_pages, d]      */

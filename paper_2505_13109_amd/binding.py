@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "fkv_arena_bytes", "fkv_create", "fkv_destroy", "fkv_last_error", "fkv_context_len", "fkv_health",
     "fkv_load_prefix", "fkv_kv_append", "fkv_page_summary_update", "fkv_corr_check",
     "fkv_page_select", "fkv_recall_pages", "fkv_sparse_decode_attn", "fkv_commit",
-    "fkv_decode_step", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_select", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
+    "fkv_decode_step", "fkv_flush", "fkv_debug_read", "fkv_debug_read_page", "fkv_profile_enable", "fkv_profile_read", "fkv_profile_attn", "fkv_profile_select", "fkv_profile_launch_floor", "fkv_step_launches", "fkv_export_nhd",
     "fkv_sparse_decode_attn_static", "fkv_recall_pending", "fkv_attach_nhd_pool", "fkv_test_lose_selection", "fkv_instrument_timestamps",
 )
 
@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
         "fkv_context_len": (C.c_int, [vp, i32]),
         "fkv_health": (C.c_int, [vp, i32]),
         "fkv_step_launches": (C.c_int, [vp, i32]),
+        "fkv_flush": (C.c_int, [vp]),
         "fkv_load_prefix": (C.c_int, [vp, i32, vp, vp, i32, vp]),
         "fkv_kv_append": (C.c_int, [vp, i32, vp, vp, vp, vp]),
         "fkv_page_summary_update": (C.c_int, [vp, i32, i32, i32, vp]),
@@ -228,6 +229,9 @@ class FreeKV:
         s = _stream(stream)
         cs = s if copy_stream is None else _stream(copy_stream)
         self._check(self.L.fkv_decode_step(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), s, cs), "fkv_decode_step")
+
+    def flush(self):
+        self._check(self.L.fkv_flush(self._h), "fkv_flush")
 
     def profile_enable(self, max_launches):
         self._check(self.L.fkv_profile_enable(self._h, max_launches), "fkv_profile_enable")

@@ -34,7 +34,10 @@ struct LayerState {
   bool staged_q = false;     // corr_check has run since the last commit
   bool have_flags = false;
   bool offload_outstanding = false;
+  bool offload_unseen = false;     // an offload the compute stream has not been made to wait for yet
   bool recall_outstanding = false;
+  bool recall_unsubmitted = false; // its deferred recall is still in the context's list, not on the copy stream yet
+  hipEvent_t recall_event = nullptr;   // what "that recall finished" is recorded in (its own ev_recall, or a later layer's)
   int recalled = 0;          // placement HOST: which heads' pending pages have been recalled (bit 0 corrected, bit 1 the others)
   int epoch = 0;             // decode steps taken through the one-launch path (selection epochs)
   int last_launches = 0;     // kernel launches of the last fkv_decode_step (compute stream)
@@ -149,6 +152,10 @@ struct fkv_ctx {
   std::string err;
   int device = 0;                     // the HIP device the context was created on
   hipEvent_t ev_fork = nullptr;
+  // Deferred recalls of one-launch layer-steps that are not submitted yet: a cross-stream dependency costs the host
+  // three HIP calls and each stream a few microseconds, so the layers of a decode step share one per kDeferGroup layers.
+  std::vector<int> deferred;
+  hipStream_t deferred_st = nullptr, deferred_cs = nullptr;
   uint16_t* nhd_pool = nullptr;       // fkv_attach_nhd_pool: recalled pages also land, converted, in this NHD pool
   int32_t* nhd_slot_pages = nullptr;
   int nhd_slots = 0;
@@ -215,8 +222,14 @@ struct fkv_ctx {
 // step finished: it reuses the miss list and flags that recall reads, and the slots it fills.
 static int wait_recall(fkv_ctx* ctx, LayerState& ls, hipStream_t st) {
   if (ls.recall_outstanding) {
-    hipError_t e = hipStreamWaitEvent(st, ls.ev_recall, 0);
-    if (e != hipSuccess) return ctx->hip_fail(e, "hipStreamWaitEvent");
+    // Usually that recall ended long ago (it had a whole decode step): then the host sees its event complete, what
+    // it wrote is visible to every later launch, and the stream needs no dependency at all.
+    hipError_t e = hipEventQuery(ls.recall_event);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();                       // "not ready" is not an error here
+      e = hipStreamWaitEvent(st, ls.recall_event, 0);
+      if (e != hipSuccess) return ctx->hip_fail(e, "hipStreamWaitEvent");
+    }
     ls.recall_outstanding = false;
   }
   return FKV_OK;
@@ -261,13 +274,21 @@ static StepIO make_step_io(fkv_ctx* ctx, int layer, const void* q, const void* k
   io.cand_key = reinterpret_cast<uint32_t*>(cb + ctx->lay.cand_key);
   io.cand_id = reinterpret_cast<int32_t*>(cb + ctx->lay.cand_id);
   io.wide_counters = reinterpret_cast<int*>(cb + ctx->lay.wide_cnt);
+  if (ctx->cfg.placement == FKV_PLACE_HOST) {      // a selection comes with its recall plan
+    io.plan_act_ids = ctx->ids(layer, ls.parity ^ 1);
+    io.plan_act_slots = ctx->slots(layer, ls.parity ^ 1);
+    io.plan_new_slots = ctx->slots(layer, ls.parity);
+    io.plan_miss = ctx->miss(layer);
+  }
   return io;
 }
 
 static int run_step(fkv_ctx* ctx, int layer, int roles, const void* q, const void* k_new, const void* v_new,
                     uint8_t* flags_user, int32_t* ids_user, int L_after, hipStream_t st) {
   const StepIO io = make_step_io(ctx, layer, q, k_new, v_new, flags_user, ids_user);
-  ctx->layers[layer].step_launches = launch_step(ctx->dims, roles, io, make_geom(ctx->cfg, L_after), st);
+  LayerState& ls = ctx->layers[layer];
+  ls.step_launches = launch_step(ctx->dims, roles, io, make_geom(ctx->cfg, L_after), st);
+  if ((roles & ROLE_SELECT) && io.plan_new_slots) ls.recalled = 0;     // a new plan: nothing of it is recalled yet
   return after_launch(ctx, "step kernel");
 }
 
@@ -286,6 +307,7 @@ static int after_append(fkv_ctx* ctx, int layer, hipStream_t st, hipStream_t cs)
     if (rc) return rc;
     FKV_HIP(ctx, hipEventRecord(ls.ev_offload, cs));
     ls.offload_outstanding = true;
+    ls.offload_unseen = cs != st;
   }
   return FKV_OK;
 }
@@ -298,6 +320,50 @@ static int run_plan(fkv_ctx* ctx, int layer, hipStream_t st) {
   ls.recalled = 0;
   return after_launch(ctx, "plan kernel");
 }
+
+// Submit the deferred recalls on the list: one dependency of the copy stream on the compute stream, one gather launch
+// for all listed layers' uncorrected heads, one event that every listed layer's next step looks at.
+constexpr int kDeferGroup = GATHER_MAX_LAYERS;
+static int flush_deferred(fkv_ctx* ctx) {
+  if (ctx->deferred.empty()) return FKV_OK;
+  hipStream_t st = ctx->deferred_st, cs = ctx->deferred_cs;
+  if (cs != st) {
+    FKV_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+    FKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->ev_fork, 0));
+  }
+  for (size_t i0 = 0; i0 < ctx->deferred.size(); i0 += GATHER_MAX_LAYERS) {
+    GatherLayers gl{};
+    for (size_t i = i0; i < ctx->deferred.size() && gl.n < GATHER_MAX_LAYERS; ++i) {
+      const int l = ctx->deferred[i];
+      gl.pd[gl.n] = ctx->pool_desc(l);
+      gl.host_pool[gl.n] = ctx->host_pool(l);
+      gl.miss[gl.n] = ctx->miss(l);
+      gl.flags[gl.n] = ctx->flags(l);
+      gl.n += 1;
+    }
+    launch_gather(ctx->dims, gl, FKV_HEADS_UNFLAGGED, cs);
+  }
+  int rc = after_launch(ctx, "gather kernel");
+  if (rc) return rc;
+  hipEvent_t done = ctx->layers[ctx->deferred.back()].ev_recall;
+  if (cs != st) FKV_HIP(ctx, hipEventRecord(done, cs));
+  for (int l : ctx->deferred) {
+    LayerState& ls = ctx->layers[l];
+    ls.recall_unsubmitted = false;
+    ls.recall_event = done;
+    ls.recall_outstanding = cs != st;
+  }
+  ctx->deferred.clear();
+  return FKV_OK;
+}
+// every entry point that looks at or changes a layer's state first submits what is on the list
+#define FKV_FLUSH(ctx)                          \
+  do {                                          \
+    if ((ctx) && !(ctx)->deferred.empty()) {    \
+      int rc_ = flush_deferred(ctx);            \
+      if (rc_) return rc_;                      \
+    }                                           \
+  } while (0)
 
 extern "C" {
 
@@ -356,10 +422,11 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   ctx->layers.resize(cfg->n_layers);
   hipError_t e = hipMemset(dev_arena, 0, l.total);
   if (e == hipSuccess) e = hipDeviceSynchronize();
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+  const unsigned ev_flags = hipEventDisableTiming;
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, ev_flags);
   for (int i = 0; e == hipSuccess && i < cfg->n_layers; ++i) {
-    e = hipEventCreateWithFlags(&ctx->layers[i].ev_offload, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->layers[i].ev_recall, hipEventDisableTiming);
+    e = hipEventCreateWithFlags(&ctx->layers[i].ev_offload, ev_flags);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->layers[i].ev_recall, ev_flags);
   }
   if (e != hipSuccess) {
     g_create_error = std::string("HIP failure in fkv_create: ") + hipGetErrorString(e);
@@ -411,6 +478,7 @@ int fkv_context_len(const fkv_ctx* ctx, int32_t layer) {
 
 int fkv_health(fkv_ctx* ctx, int32_t layer) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   int flag = 0;
   FKV_HIP(ctx, hipDeviceSynchronize());
   FKV_HIP(ctx, hipMemcpy(&flag, ctx->status(layer), sizeof(int), hipMemcpyDeviceToHost));
@@ -423,6 +491,7 @@ int fkv_health(fkv_ctx* ctx, int32_t layer) {
 
 int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* V_dev, int32_t n_tokens, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (n_tokens < 0 || n_tokens > ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "n_tokens exceeds max_ctx");
   if (n_tokens > 0 && (!K_dev || !V_dev)) return ctx->fail(FKV_EINVAL, "null K or V");
   LayerState& ls = ctx->layers[layer];
@@ -445,6 +514,7 @@ int fkv_load_prefix(fkv_ctx* ctx, int32_t layer, const void* K_dev, const void* 
 
 int fkv_kv_append(fkv_ctx* ctx, int32_t layer, const void* k_new_dev, const void* v_new_dev, void* stream, void* copy_stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!k_new_dev || !v_new_dev) return ctx->fail(FKV_EINVAL, "null k_new or v_new");
   LayerState& ls = ctx->layers[layer];
   if (ls.L >= ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "append beyond max_ctx");
@@ -456,6 +526,7 @@ int fkv_kv_append(fkv_ctx* ctx, int32_t layer, const void* k_new_dev, const void
 
 int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int32_t n_pages, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (ctx->cfg.placement != FKV_PLACE_HBM) return ctx->fail(FKV_ESTATE, "summary recompute needs the keys in HBM");
   LayerState& ls = ctx->layers[layer];
   const int n_have = (ls.L + PG - 1) / PG;
@@ -467,6 +538,7 @@ int fkv_page_summary_update(fkv_ctx* ctx, int32_t layer, int32_t first_page, int
 
 int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flags_dev, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!q_dev) return ctx->fail(FKV_EINVAL, "null q");
   LayerState& ls = ctx->layers[layer];
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -481,6 +553,7 @@ int fkv_corr_check(fkv_ctx* ctx, int32_t layer, const void* q_dev, uint8_t* flag
 
 int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* page_ids_dev, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!q_dev) return ctx->fail(FKV_EINVAL, "null q");
   LayerState& ls = ctx->layers[layer];
   if (ls.L < 1) return ctx->fail(FKV_ESTATE, "empty context");
@@ -488,8 +561,6 @@ int fkv_page_select(fkv_ctx* ctx, int32_t layer, const void* q_dev, int32_t* pag
   int rc = wait_recall(ctx, ls, st);
   if (rc) return rc;
   rc = run_step(ctx, layer, ROLE_SELECT, q_dev, nullptr, nullptr, nullptr, page_ids_dev, ls.L, st);
-  if (rc) return rc;
-  rc = run_plan(ctx, layer, st);
   if (rc) return rc;
   ls.have_pending = true;
   return FKV_OK;
@@ -531,13 +602,16 @@ static int recall_missing(fkv_ctx* ctx, int layer, int heads_mode, const uint8_t
                       ctx->nhd_pool, ctx->nhd_slots, make_geom(ctx->cfg, ls.L).n_sink, cs);
     return after_launch(ctx, "streamed NHD gather kernel");
   }
-  launch_gather(ctx->dims, ctx->pool_desc(layer), ctx->host_pool(layer), ctx->miss(layer), nullptr,
-                select_by, heads_mode, cs);
+  GatherLayers gl{};
+  gl.n = 1;
+  gl.pd[0] = ctx->pool_desc(layer); gl.host_pool[0] = ctx->host_pool(layer); gl.miss[0] = ctx->miss(layer); gl.flags[0] = select_by;
+  launch_gather(ctx->dims, gl, heads_mode, cs);
   return after_launch(ctx, "gather kernel");
 }
 
 int fkv_recall_pending(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (heads < 0 || heads > 2) return ctx->fail(FKV_EINVAL, "bad heads selector");
   if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
   LayerState& ls = ctx->layers[layer];
@@ -551,6 +625,7 @@ int fkv_recall_pending(fkv_ctx* ctx, int32_t layer, int32_t heads, void* copy_st
 
 int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, const int32_t* page_ids_dev, const uint8_t* head_mask_dev, void* copy_stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (ctx->cfg.placement != FKV_PLACE_HOST) return FKV_OK;
   LayerState& ls = ctx->layers[layer];
   hipStream_t cs = static_cast<hipStream_t>(copy_stream);
@@ -575,6 +650,7 @@ int fkv_recall_pages(fkv_ctx* ctx, int32_t layer, const int32_t* page_ids_dev, c
 
 int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev, int32_t use, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!q_dev || !out_dev) return ctx->fail(FKV_EINVAL, "null q or out");
   if (use < 0 || use > 2) return ctx->fail(FKV_EINVAL, "bad use selector");
   LayerState& ls = ctx->layers[layer];
@@ -599,6 +675,7 @@ int fkv_sparse_decode_attn(fkv_ctx* ctx, int32_t layer, const void* q_dev, float
 
 int fkv_sparse_decode_attn_static(fkv_ctx* ctx, int32_t layer, const void* q_dev, float* out_dev, int32_t use, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!q_dev || !out_dev) return ctx->fail(FKV_EINVAL, "null q or out");
   if (use < 0 || use > 2) return ctx->fail(FKV_EINVAL, "bad use selector");
   LayerState& ls = ctx->layers[layer];
@@ -639,6 +716,7 @@ int fkv_sparse_decode_attn_static(fkv_ctx* ctx, int32_t layer, const void* q_dev
 int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev, int32_t* slot_pages_dev,
                    int32_t n_slots, void* stream) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!nhd_pool_dev || !slot_pages_dev) return ctx->fail(FKV_EINVAL, "null output");
   if (use < 0 || use > 2) return ctx->fail(FKV_EINVAL, "bad use selector");
   const fkv_config& c = ctx->cfg;
@@ -660,6 +738,7 @@ int fkv_export_nhd(fkv_ctx* ctx, int32_t layer, int32_t use, void* nhd_pool_dev,
 
 int fkv_attach_nhd_pool(fkv_ctx* ctx, void* nhd_pool_dev, int32_t* slot_pages_dev, int32_t n_slots) {
   if (!ctx) return FKV_EINVAL;
+  FKV_FLUSH(ctx);
   if (!nhd_pool_dev) {
     ctx->nhd_pool = nullptr; ctx->nhd_slot_pages = nullptr; ctx->nhd_slots = 0;
     return FKV_OK;
@@ -676,8 +755,7 @@ int fkv_attach_nhd_pool(fkv_ctx* ctx, void* nhd_pool_dev, int32_t* slot_pages_de
   return FKV_OK;
 }
 
-int fkv_commit(fkv_ctx* ctx, int32_t layer) {
-  FKV_CHECK_LAYER(ctx, layer);
+static int commit_layer(fkv_ctx* ctx, int32_t layer) {
   LayerState& ls = ctx->layers[layer];
   if (!ls.have_pending || !ls.staged_q) return ctx->fail(FKV_ESTATE, "commit needs corr_check and page_select first");
   if (ctx->cfg.placement == FKV_PLACE_HOST && ctx->lay.k > 0 && ls.recalled != 3)
@@ -691,6 +769,17 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer) {
   return FKV_OK;
 }
 
+int fkv_commit(fkv_ctx* ctx, int32_t layer) {
+  FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
+  return commit_layer(ctx, layer);
+}
+
+int fkv_flush(fkv_ctx* ctx) {
+  if (!ctx) return FKV_EINVAL;
+  return flush_deferred(ctx);
+}
+
 int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev, const void* v_new_dev,
                     float* out_dev, void* compute_stream, void* copy_stream) {
   FKV_CHECK_LAYER(ctx, layer);
@@ -699,10 +788,21 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   hipStream_t st = static_cast<hipStream_t>(compute_stream);
   hipStream_t cs = static_cast<hipStream_t>(copy_stream);
   if (ls.L >= ctx->cfg.max_ctx) return ctx->fail(FKV_ERANGE, "append beyond max_ctx");
-  int rc = wait_recall(ctx, ls, st);
+  int rc = FKV_OK;
+  if (!ctx->deferred.empty() && (ls.recall_unsubmitted || st != ctx->deferred_st || cs != ctx->deferred_cs)) {
+    rc = flush_deferred(ctx);      // this layer's own recall of the last step is still on the list, or the streams changed
+    if (rc) return rc;
+  }
+  rc = wait_recall(ctx, ls, st);
   if (rc) return rc;
-  if (ctx->cfg.placement == FKV_PLACE_HBM) {
-    // everything in one launch when the shape allows it
+  const bool host_pool = ctx->cfg.placement == FKV_PLACE_HOST;
+  // everything in one launch when the shape allows it; with the host pool, when the recall is the library's gather into
+  // its own page cache (the kernel's attention blocks then fetch a corrected head's missing pages themselves)
+  if (!host_pool || (ctx->cfg.recall_mode == FKV_RECALL_GATHER && !ctx->nhd_pool)) {
+    if (host_pool && ls.offload_unseen) {      // a page offloaded moments ago may be picked, and missed, already
+      FKV_HIP(ctx, hipStreamWaitEvent(st, ls.ev_offload, 0));
+      ls.offload_unseen = false;
+    }
     const StepIO io = make_step_io(ctx, layer, q_dev, k_new_dev, v_new_dev, nullptr, nullptr);
     LayerIO lio{};
     lio.act_ids = ctx->ids(layer, ls.parity ^ 1);
@@ -711,6 +811,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     lio.max_splits = ctx->lay.max_splits;
     lio.attn_counters = ctx->attn_counters(layer);
     lio.out = out_dev;
+    lio.host_pool = host_pool ? ctx->host_pool(layer) : nullptr;
     lio.tagged = ctx->tagged(layer);
     lio.epoch = ls.epoch + 1;
     lio.status = ctx->status(layer);
@@ -729,9 +830,27 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
       if (rc) return rc;
       ls.epoch += 1;
       ls.last_launches = 1;
-      ls.L += 1;
+      ls.step_launches = 1;
       ls.staged_q = ls.have_flags = ls.have_pending = true;
-      return fkv_commit(ctx, layer);
+      if (!host_pool) {
+        ls.L += 1;
+        return commit_layer(ctx, layer);
+      }
+      rc = after_append(ctx, layer, st, cs);
+      if (rc) return rc;
+      // The corrected heads' pages are in their slots when the kernel ends.  The other heads' recall, for the next
+      // step (Sec. 3.2), goes to the copy stream; it writes only slots that no attention of this step reads.  It is
+      // put on the context's list and submitted together with the next layers' (flush_deferred).
+      ls.recalled = 3;
+      ls.recall_unsubmitted = true;
+      ctx->deferred.push_back(layer);
+      ctx->deferred_st = st;
+      ctx->deferred_cs = cs;
+      if ((int)ctx->deferred.size() >= kDeferGroup || layer == ctx->cfg.n_layers - 1) {
+        rc = flush_deferred(ctx);
+        if (rc) return rc;
+      }
+      return commit_layer(ctx, layer);
     }
   }
   // append + correction test + selection for all heads: one launch
@@ -740,10 +859,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
   if (rc) return rc;
   rc = after_append(ctx, layer, st, cs);
   if (rc) return rc;
-  rc = run_plan(ctx, layer, st);
-  if (rc) return rc;
   ls.staged_q = ls.have_flags = ls.have_pending = true;
-  const bool host_pool = ctx->cfg.placement == FKV_PLACE_HOST;
   bool deferred = false;
   if (host_pool) {
     // corrected heads: recall before this step's attention (Sec. 3.3)
@@ -759,6 +875,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
       rc = fkv_recall_pending(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
       if (rc) return rc;
       FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
+      ls.recall_event = ls.ev_recall;
       deferred = true;     // the next step of this layer waits for it, not this step's attention
     }
   }
@@ -778,9 +895,9 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
     if (rc) return rc;
   }
   ls.recall_outstanding = deferred;
-  // step roles (1-3) + attention, and with the host pool the plan and the corrected heads' gather
-  ls.last_launches = ls.step_launches + 1 + (host_pool ? 2 : 0);
-  return fkv_commit(ctx, layer);
+  // step roles (1-4, the recall plan rides with the selection) + attention, and with the host pool the corrected heads' gather
+  ls.last_launches = ls.step_launches + 1 + (host_pool ? 1 : 0);
+  return commit_layer(ctx, layer);
 }
 
 int fkv_test_lose_selection(fkv_ctx* ctx, int32_t on) {
@@ -827,6 +944,7 @@ int fkv_profile_read(fkv_ctx* ctx, double* total_ms, int32_t* launches) {
 int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, float* out_dev, int32_t reps,
                      void* stream, double* total_ms, int32_t* launches) {
   if (!ctx || !q_dev || !out_dev || !total_ms || !launches || reps < 1) return FKV_EINVAL;
+  FKV_FLUSH(ctx);
   hipStream_t st = static_cast<hipStream_t>(stream);
   for (int l = 0; l < ctx->cfg.n_layers; ++l)
     if (ctx->layers[l].L < 1 || !ctx->layers[l].have_active) return ctx->fail(FKV_ESTATE, "every layer needs a context and an active selection");
@@ -861,6 +979,7 @@ int fkv_profile_attn(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, flo
 int fkv_profile_select(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, int32_t reps, void* stream,
                        double* total_ms, int32_t* launches) {
   if (!ctx || !q_dev || !total_ms || !launches || reps < 1) return FKV_EINVAL;
+  FKV_FLUSH(ctx);
   hipStream_t st = static_cast<hipStream_t>(stream);
   for (int l = 0; l < ctx->cfg.n_layers; ++l)
     if (ctx->layers[l].L < 1) return ctx->fail(FKV_ESTATE, "every layer needs a context");
@@ -892,6 +1011,7 @@ int fkv_profile_select(fkv_ctx* ctx, const void* q_dev, size_t q_layer_stride, i
 int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* stream, double* total_ms,
                              int32_t* grid, int32_t* lds_bytes) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!total_ms || reps < 1) return ctx->fail(FKV_EINVAL, "bad argument");
   const LayerState& ls = ctx->layers[layer];
   if (ls.last_launches != 1 || ls.last_grid < 1) return ctx->fail(FKV_ESTATE, "the layer's last step was not a single launch");
@@ -919,6 +1039,7 @@ int fkv_profile_launch_floor(fkv_ctx* ctx, int32_t layer, int32_t reps, void* st
 
 int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, size_t bytes) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   if (!host_out) return ctx->fail(FKV_EINVAL, "null output");
   const fkv_config& c = ctx->cfg;
   const LayerState& ls = ctx->layers[layer];
@@ -958,6 +1079,7 @@ int fkv_debug_read(fkv_ctx* ctx, int32_t layer, int32_t what, void* host_out, si
 
 int fkv_debug_read_page(fkv_ctx* ctx, int32_t layer, int32_t request, int32_t kv_head, int32_t page, int32_t where, void* host_out) {
   FKV_CHECK_LAYER(ctx, layer);
+  FKV_FLUSH(ctx);
   const fkv_config& c = ctx->cfg;
   if (!host_out) return ctx->fail(FKV_EINVAL, "null output");
   if (request < 0 || request >= c.batch || kv_head < 0 || kv_head >= c.n_kv_heads) return ctx->fail(FKV_ERANGE, "request or head out of range");

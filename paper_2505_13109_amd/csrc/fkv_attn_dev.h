@@ -88,6 +88,10 @@ struct AttnArgs {
   const unsigned long long* tagged;   // [heads][k]: this step's picked ids as (epoch << 32 | id), written by the selection
   int epoch;
   int* status;               // set to 1 if a wait ran out
+  // fused, KV in a host pool: the tagged words are tagged_pick() values; a corrected head's wave copies a missing page
+  // from the host pool into its slot while it attends over it
+  const uint16_t* host_pool; // [heads][max_pages] units
+  int max_pages;
 };
 
 template <int CH> struct MergeChunk { static constexpr int value = CH; };
@@ -121,7 +125,9 @@ __device__ __forceinline__ int attend_unit(const AttendList& al, const PoolDesc&
 
 // One block of NW wavefronts: attend-list positions [split*pps, (split+1)*pps) of head (b, m),
 // wave w takes w, w+NW, ...  `lds` is at least NW*(32 + G*128) floats when NW > 1.
-template <int DT, int NW>
+// HOSTFUSED: the variant for a fused launch with the KV in a host pool (a compile-time choice: what it adds to the page
+// loop would cost the other launches registers).
+template <int DT, int NW, bool HOSTFUSED = false>
 __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, int b, float* lds) {
   typedef typename Mma<DT>::vec vec;
   const PoolDesc& pd = a.pd;
@@ -205,11 +211,15 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   for (int phase = 0; phase < (two_phase ? 2 : 1); ++phase) {
     // first position of this wave, from `from` on, that belongs to the phase and holds a page
     int n_valid = PG, page = -1;
-    auto find = [&](int from, int& nv, int& pg) -> int2 {
+    // a position's page: where in the attend list, which unit of the head's pool, where its bytes are read from, and
+    // whether they come from the host pool and have to be put into that unit on the way
+    struct Pick { int pos, unit; const uint16_t* src; bool fill; };
+    auto find = [&](int from, int& nv, int& pg) -> Pick {
       for (int p2 = from; p2 < p_end; p2 += NW) {
         if (two_phase && ((p2 >= pk_lo && p2 < pk_hi) != (phase == 1))) continue;
         bool have_id = spec && !pending && p2 == pos0;
-        int id = spec_id;
+        int id = spec_id, slot = -1;
+        bool miss = false;
         if (two_phase && phase == 1) {
           // Wait for this step's id of the position: the selection writes every picked id as one 64-bit
           // word tagged with the step's epoch.  The block that makes it is one of the scoring blocks of
@@ -229,20 +239,31 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
             break;                                             // the id is not there: read nothing
           }
           have_id = true;
-          id = (int)(uint32_t)w2;
+          if constexpr (HOSTFUSED) tagged_unpick((uint32_t)w2, id, slot, miss);
+          else id = (int)(uint32_t)w2;
+        }
+        if (HOSTFUSED && slot >= 0) {
+          // KV in a host pool, this step's selection: the slot came with the id (the slot table in memory is being
+          // written by another block of this launch); a page the cache does not hold is read from the host pool
+          nv = PG;
+          pg = id;
+          const int u = pd.sel_base + slot;
+          const uint16_t* from_pool = head_pool + (size_t)u * UNIT_ELEMS;
+          return Pick{p2, u, miss ? a.host_pool + ((size_t)head * a.max_pages + id) * UNIT_ELEMS : from_pool, miss};
         }
         const int u = attend_unit(al, pd, p2, nv, pg, have_id, id);
-        if (u >= 0) return make_int2(p2, u);
+        if (u >= 0) return Pick{p2, u, head_pool + (size_t)u * UNIT_ELEMS, false};
       }
-      return make_int2(p_end, -1);
+      return Pick{p_end, -1, nullptr, false};
     };
     // Page loop, software-pipelined: the 16 wave-loads of the next page are issued before the
     // MFMAs of the current one, so a wave that owns several pages keeps 32 KiB in flight.
-    int2 cur = find(pos0, n_valid, page);
-    int pos = cur.x, unit = cur.y;
+    const Pick cur = find(pos0, n_valid, page);
+    int pos = cur.pos, unit = cur.unit;
+    bool fill = cur.fill;
   uint4 kw[8], vw[8];
   if (unit >= 0) {
-    const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)unit * UNIT_ELEMS) + lane;
+    const uint4* up = reinterpret_cast<const uint4*>(cur.src) + lane;
 #pragma unroll
     for (int j = 0; j < 8; ++j) kw[j] = up[j * 64];
 #pragma unroll
@@ -251,15 +272,24 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   while (unit >= 0) {
     // next page of this wave, if any
     int nn_valid = PG, npage = -1;
-    const int2 nxt = find(pos + NW, nn_valid, npage);
-    const int npos = nxt.x, nunit = nxt.y;
+    const Pick nxt = find(pos + NW, nn_valid, npage);
+    const int npos = nxt.pos, nunit = nxt.unit;
     uint4 kn[8], vn[8];
     if (nunit >= 0) {
-      const uint4* up = reinterpret_cast<const uint4*>(head_pool + (size_t)nunit * UNIT_ELEMS) + lane;
+      const uint4* up = reinterpret_cast<const uint4*>(nxt.src) + lane;
 #pragma unroll
       for (int j = 0; j < 8; ++j) kn[j] = up[j * 64];
 #pragma unroll
       for (int j = 0; j < 8; ++j) vn[j] = up[(8 + j) * 64];
+    }
+    if (HOSTFUSED && fill) {
+      // the page came from the host pool: it goes into its page-cache slot as it is (recall, Sec. 3.3: a corrected
+      // head's pages are fetched before it attends; here the wave that attends over the page is the one that fetches it)
+      uint4* dp = reinterpret_cast<uint4*>(pd.pool + ((size_t)head * pd.units_per_head + unit) * UNIT_ELEMS) + lane;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dp[j * 64] = kw[j];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dp[(8 + j) * 64] = vw[j];
     }
     if (page == new_page) {
       // overwrite the new token's key row and value column with the step's inputs
@@ -327,7 +357,7 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
       acc[cb] = Mma<DT>::mma(va, phi, acc[cb]);
       acc[cb] = Mma<DT>::mma(va, plo, acc[cb]);
     }
-    pos = npos; unit = nunit; n_valid = nn_valid; page = npage;
+    pos = npos; unit = nunit; n_valid = nn_valid; page = npage; fill = nxt.fill;
     if (nunit >= 0) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) { kw[j] = kn[j]; vw[j] = vn[j]; }

@@ -1,5 +1,6 @@
 // Data-plane kernels: bulk context load, summary recompute, page offload to / recall from the host pool.
 #include "fkv_device.h"
+#include "fkv_plan_dev.h"
 
 namespace fkv {
 
@@ -115,31 +116,35 @@ __global__ __launch_bounds__(256) void offload_kernel(PoolDesc pd, uint16_t* __r
 constexpr int GATHER_THREADS = 1024;
 constexpr int GATHER_BLOCKS = 16;            // measured: 8 and 16 blocks move 52-53 GB/s, 24 blocks 50, 32 blocks 47
 constexpr int GATHER_UNITS = 4;              // units in flight per block (8 is no faster)
-__global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(PoolDesc pd, const uint16_t* __restrict__ host_pool,
-                                                                const int32_t* __restrict__ miss,
-                                                                const uint8_t* __restrict__ flags, int heads_mode,
+// One launch serves the miss lists of up to GATHER_MAX_LAYERS layers (the deferred recall of several layers is
+// submitted together); a "head" below is a (layer, KV head) pair, numbered layer-major.
+__global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(GatherLayers gl, int heads_mode,
                                                                 int k, int n_kv, int n_heads, int max_pages) {
-  extern __shared__ int32_t chunks_of[];     // [n_heads]: 4-unit chunks this launch moves for each head
+  extern __shared__ int32_t chunks_of[];     // [n_layers * n_heads]: 4-unit chunks this launch moves for each head
   const int tid = threadIdx.x;
+  const int n_all = gl.n * n_heads;
   // The chunks (GATHER_UNITS units each) of all chosen heads, numbered through, are dealt to the blocks in turn, so that every
   // block moves the same amount whatever the heads' miss counts are (a corrected-heads launch
   // serves about every other head, with anything from 0 to k misses).
-  for (int head = tid; head < n_heads; head += GATHER_THREADS) {
-    const bool chosen = heads_mode == 0 || ((heads_mode == 1) == (flags[head] != 0));
-    chunks_of[head] = chosen ? (miss[(size_t)head * (1 + 3 * k)] + GATHER_UNITS - 1) / GATHER_UNITS : 0;
+  for (int h = tid; h < n_all; h += GATHER_THREADS) {
+    const int li = h / n_heads, head = h % n_heads;
+    const bool chosen = heads_mode == 0 || ((heads_mode == 1) == (gl.flags[li][head] != 0));
+    chunks_of[h] = chosen ? (gl.miss[li][(size_t)head * (1 + 3 * k)] + GATHER_UNITS - 1) / GATHER_UNITS : 0;
   }
   __syncthreads();
   int first = 0;                                // number of the head's first chunk
-  for (int head = 0; head < n_heads; ++head) {
-    const int n_chunks = chunks_of[head];
+  for (int h = 0; h < n_all; ++h) {
+    const int n_chunks = chunks_of[h];
     const int c_begin = first;
     first += n_chunks;
     // chunks of this head that are this block's: c_begin + j with (c_begin + j) % gridDim.x == blockIdx.x
     int j = ((int)blockIdx.x - c_begin % (int)gridDim.x + (int)gridDim.x) % (int)gridDim.x;
     if (j >= n_chunks) continue;
-    const int32_t* mh = miss + (size_t)head * (1 + 3 * k);
+    const int li = h / n_heads, head = h % n_heads;
+    const PoolDesc& pd = gl.pd[li];
+    const int32_t* mh = gl.miss[li] + (size_t)head * (1 + 3 * k);
     const int n = mh[0];
-    const uint16_t* src_head = host_pool + (size_t)head * max_pages * UNIT_ELEMS;
+    const uint16_t* src_head = gl.host_pool[li] + (size_t)head * max_pages * UNIT_ELEMS;
     uint16_t* dst_head = pd.pool + ((size_t)head * pd.units_per_head + pd.sel_base) * UNIT_ELEMS;
     for (; j < n_chunks; j += gridDim.x) {
       const int i0 = j * GATHER_UNITS;
@@ -254,85 +259,16 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_nhd_kernel(PoolDesc pd,
   }
 }
 
-// ---- recall plan: which picked pages are already cached, where the others go ------
-// A page hits iff it is in the ACTIVE selection (it keeps that slot).  Misses go, in
-// ascending page order, to the lowest-numbered slots the ACTIVE selection does not use.
-// grid (n_kv, batch), 64 threads (one wave); pool of 2k slots per head; k <= 1024.
-// An id that is not a full page of the context (a caller's list may hold anything) is dropped:
-// rewritten to -1 in new_ids, so that neither the gather nor attention ever forms its address.
+// ---- recall plan (fkv_plan_dev.h) as a launch of its own: grid (n_kv, batch), one wave ------------
 __global__ __launch_bounds__(64) void plan_kernel(int32_t* __restrict__ new_ids,
                                                   const int32_t* __restrict__ act_ids,
                                                   const int32_t* __restrict__ act_slots,
                                                   int32_t* __restrict__ new_slots,
                                                   int32_t* __restrict__ miss, int k, int n_kv, int n_full) {
-  extern __shared__ int32_t sm[];          // used[2k], aid[k], aslot[k], nid[k], nslot[k], freelist[2k]
-  int32_t* used = sm;
-  int32_t* aid = sm + 2 * k;
-  int32_t* aslot = aid + k;
-  int32_t* nid = aslot + k;
-  int32_t* nslot = nid + k;
-  int32_t* freelist = nslot + k;
-  const int m = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-  const size_t hb = (size_t)(b * n_kv + m) * k;
-  int32_t* mh = miss + (size_t)(b * n_kv + m) * (1 + 3 * k);
-  for (int s = lane; s < 2 * k; s += 64) used[s] = 0;
-  int n_act = 0;
-  for (int i = lane; i < k; i += 64) {     // all lists in one round trip
-    aid[i] = act_ids[hb + i];
-    aslot[i] = act_slots[hb + i];
-    const int32_t id = new_ids[hb + i];
-    nid[i] = id < n_full ? id : -1;
-    if (id >= n_full) new_ids[hb + i] = -1;
-  }
-  __syncthreads();
-  for (int i = lane; i < k; i += 64) {
-    if (aid[i] >= 0) { used[aslot[i]] = 1; ++n_act; }
-  }
-  n_act = (int)wave_sum_u32((uint32_t)n_act);   // ids are ascending, -1 padded at the end
-  __syncthreads();
-  // hit or miss per picked page (binary search in the ACTIVE ids)
-  for (int i = lane; i < k; i += 64) {
-    const int id = nid[i];
-    int slot = -1;
-    if (id >= 0) {
-      int lo = 0, hi = n_act;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (aid[mid] < id) lo = mid + 1; else hi = mid;
-      }
-      slot = (lo < n_act && aid[lo] == id) ? aslot[lo] : -2;   // -2: miss
-    }
-    nslot[i] = slot;
-  }
-  // ordered list of free slots
-  int base = 0;
-  for (int s0 = 0; s0 < 2 * k; s0 += 64) {
-    const int s = s0 + lane;
-    const uint32_t f = (s < 2 * k && !used[s]) ? 1u : 0u;
-    const uint32_t incl = wave_scan_u32(f);
-    if (f) freelist[base + (int)incl - 1] = s;
-    base += (int)__builtin_amdgcn_readlane((int)incl, 63);
-  }
-  __syncthreads();
-  // the r-th miss (ascending page id) takes the r-th free slot
-  int n_miss = 0;
-  for (int i0 = 0; i0 < k; i0 += 64) {
-    const int i = i0 + lane;
-    const uint32_t f = (i < k && nslot[i] == -2) ? 1u : 0u;
-    const uint32_t incl = wave_scan_u32(f);
-    if (f) {
-      const int r = n_miss + (int)incl - 1;
-      const int s = freelist[r];
-      nslot[i] = s;
-      mh[1 + r] = nid[i];
-      mh[1 + k + r] = s;
-      mh[1 + 2 * k + r] = i;
-    }
-    n_miss += (int)__builtin_amdgcn_readlane((int)incl, 63);
-  }
-  if (lane == 0) mh[0] = n_miss;
-  __syncthreads();
-  for (int i = lane; i < k; i += 64) new_slots[hb + i] = nslot[i];
+  extern __shared__ int32_t sm[];
+  const size_t head = (size_t)blockIdx.y * n_kv + blockIdx.x;
+  plan_head<64>(new_ids + head * k, act_ids + head * k, act_slots + head * k, new_slots + head * k,
+                miss + head * (1 + 3 * k), k, n_full, sm, false);
 }
 
 // ---- debug: one unit -> token-major K [p, d], V [p, d] ---------------------------
@@ -373,12 +309,11 @@ void launch_plan(const Dims& d, int32_t* new_ids, const int32_t* act_ids, const 
                  int32_t* new_slots, int32_t* miss, int n_full, hipStream_t st) {
   if (d.k == 0) return;
   dim3 grid(d.n_kv, d.batch);
-  plan_kernel<<<grid, 64, 8 * d.k * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv, n_full);
+  plan_kernel<<<grid, 64, plan_lds_ints(d.k) * sizeof(int32_t), st>>>(new_ids, act_ids, act_slots, new_slots, miss, d.k, d.n_kv, n_full);
 }
 
-void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
-                   const int32_t*, const uint8_t* flags, int heads, hipStream_t st) {
-  if (d.k == 0) return;
+void launch_gather(const Dims& d, const GatherLayers& gl, int heads, hipStream_t st) {
+  if (d.k == 0 || gl.n <= 0) return;
   static bool raised = false;
   const int hog = d.max_lds > 64 * 1024 ? d.max_lds - 1024 : 64 * 1024 - 1024;   // (nearly) all of a unit's LDS
   if (!raised) {
@@ -387,8 +322,19 @@ void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool,
     raised = true;
   }
   const int n_heads = d.batch * d.n_kv;
-  const int blocks = n_heads < GATHER_BLOCKS ? n_heads : GATHER_BLOCKS;
-  gather_kernel<<<blocks, GATHER_THREADS, hog, st>>>(pd, host_pool, miss, flags, heads, d.k, d.n_kv, n_heads, d.max_pages);
+  // the kernel keeps one counter per (layer, head) in LDS: as many layers per launch as fit
+  int per_launch = (int)((size_t)hog / sizeof(int32_t) / (size_t)n_heads);
+  if (per_launch < 1) per_launch = 1;        // (fkv_create bounds the heads so that one layer always fits)
+  for (int l0 = 0; l0 < gl.n; l0 += per_launch) {
+    GatherLayers part{};
+    part.n = gl.n - l0 < per_launch ? gl.n - l0 : per_launch;
+    for (int i = 0; i < part.n; ++i) {
+      part.pd[i] = gl.pd[l0 + i]; part.host_pool[i] = gl.host_pool[l0 + i];
+      part.miss[i] = gl.miss[l0 + i]; part.flags[i] = gl.flags[l0 + i];
+    }
+    const int blocks = n_heads * part.n < GATHER_BLOCKS ? n_heads * part.n : GATHER_BLOCKS;
+    gather_kernel<<<blocks, GATHER_THREADS, hog, st>>>(part, heads, d.k, d.n_kv, n_heads, d.max_pages);
+  }
 }
 
 void launch_gather_nhd(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,

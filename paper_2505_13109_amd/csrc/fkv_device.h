@@ -136,6 +136,20 @@ __device__ __forceinline__ float2 ld_dev2(const float* p) {
   return make_float2(__uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
 }
 
+// A picked page as one 32-bit value, for the exchange between the selecting block and waiting attention waves when the
+// KV lives in a host pool: page id (< 2^16), page-cache slot (< 2^15), and whether the slot has yet to be filled from
+// the host pool; all ones: no page at this position.
+constexpr int TAGGED_MAX_PAGES = 1 << 16, TAGGED_MAX_SLOTS = 1 << 15;
+__device__ __forceinline__ uint32_t tagged_pick(int id, int slot, bool miss) {
+  return id < 0 ? 0xffffffffu : ((miss ? 0x80000000u : 0u) | ((uint32_t)slot << 16) | (uint32_t)id);
+}
+__device__ __forceinline__ void tagged_unpick(uint32_t w, int& id, int& slot, bool& miss) {
+  if (w == 0xffffffffu) { id = -1; slot = -1; miss = false; return; }
+  id = (int)(w & 0xffffu);
+  slot = (int)((w >> 16) & 0x7fffu);
+  miss = (w >> 31) != 0;
+}
+
 // All vector-memory operations this wave has issued so far -- loads and stores count on the same
 // counter on this target -- have completed.  For a store issued at device scope (st_dev*: written
 // through to the device coherence point) "completed" means it is visible to every compute unit of

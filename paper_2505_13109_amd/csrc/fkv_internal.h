@@ -76,6 +76,9 @@ struct StepIO {
   long long* tstamp;                                                                 // debug timestamps or null
   // scratch of a selection spread over several blocks per head (all may be null: then it is never spread)
   float* bmax; int bmax_stride; float* hmax; unsigned long long* zsum; uint32_t* cand_key; int32_t* cand_id; int* wide_counters;
+  // KV in a host pool (else all null): a launch with ROLE_SELECT also makes the recall plan of the new selection --
+  // ACTIVE ids and slots in, PENDING slots and miss lists out
+  const int32_t* plan_act_ids; const int32_t* plan_act_slots; int32_t* plan_new_slots; int32_t* plan_miss;
 };
 constexpr int WIDE_MAX_SLICES = 16;       // most blocks that share one head's selection
 bool wide_plan(const Dims& d, const Geom& g, int* B, int* slice);
@@ -85,6 +88,7 @@ int launch_step(const Dims& d, int roles, const StepIO& io, Geom g, hipStream_t 
 // has to take the separate launches
 struct LayerIO {
   const int32_t* act_ids; float* part_o; float* part_ml; int max_splits; int* attn_counters; float* out;
+  const uint16_t* host_pool;                 // KV in a host pool: this layer's pool (corrected heads fetch their missing pages from it)
   unsigned long long* tagged; int epoch; int* status;   // tagged: [heads][k] epoch-tagged copies of the picked ids
   int attn_epoch_bias;                       // 0; a test of the bounded wait makes attention wait for an epoch that never comes
   int* launch_grid; size_t* launch_lds;      // out (may be null): shape of the launch that was made
@@ -101,8 +105,17 @@ void launch_offload(const Dims& d, const PoolDesc& pd, uint16_t* host_pool, int 
 // new_ids is read and, where an id is not a full page (id < 0 or id >= n_full), rewritten to -1
 void launch_plan(const Dims& d, int32_t* new_ids, const int32_t* act_ids, const int32_t* act_slots,
                  int32_t* new_slots, int32_t* miss, int n_full, hipStream_t st);
-void launch_gather(const Dims& d, const PoolDesc& pd, const uint16_t* host_pool, const int32_t* miss,
-                   const int32_t* new_slots_unused, const uint8_t* flags, int heads, hipStream_t st);
+// recall of missing pages, host pool -> page-cache slots, for up to GATHER_MAX_LAYERS layers in one launch;
+// heads: FKV_HEADS_* (all, flagged only, unflagged only -- by each layer's own flags)
+constexpr int GATHER_MAX_LAYERS = 8;
+struct GatherLayers {
+  int n;
+  PoolDesc pd[GATHER_MAX_LAYERS];
+  const uint16_t* host_pool[GATHER_MAX_LAYERS];
+  const int32_t* miss[GATHER_MAX_LAYERS];
+  const uint8_t* flags[GATHER_MAX_LAYERS];
+};
+void launch_gather(const Dims& d, const GatherLayers& gl, int heads, hipStream_t st);
 // returns the number of splits written per KV head
 int  launch_attn(const Dims& d, const PoolDesc& pd, const uint16_t* q, const int32_t* act_ids,
                  const int32_t* new_ids, const int32_t* act_slots, const int32_t* new_slots,

@@ -100,6 +100,17 @@ static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, si
   const bool wide = wp.ok && select && !a.fuse_select;
   a.bmax = wide ? wp.io->bmax : nullptr;
   a.bmax_stride = wp.io->bmax_stride;
+  // the recall plan rides at the end of the selecting block's LDS; a spread selection is followed by the plan kernel
+  const bool plan = select && a.plan_new_slots != nullptr;
+  const size_t plan_bytes = plan ? plan_lds_ints(a.k) * sizeof(int32_t) : 0;
+  a.plan_lds_off = (int)((lds - plan_bytes) / sizeof(uint32_t));
+  int32_t* const plan_slots = a.plan_new_slots;
+  auto plan_after_wide = [&]() -> int {
+    if (!plan) return 0;
+    launch_plan(*wp.d, a.ids, a.plan_act_ids, a.plan_act_slots, plan_slots, a.plan_miss, a.g.n_full, st);
+    return 1;
+  };
+  if (wide) a.plan_new_slots = nullptr;
   if (select && !a.fuse_select && g_scan_kernel) {
     // the selection does not ride along: the roles go to the scan kernel, one 64-page chunk per 256-thread block
     StepArgs sa = a;
@@ -113,7 +124,7 @@ static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, si
       scan_kernel<DT, G><<<sgrid, SCAN_WAVES * 64, 0, st>>>(sa);
       if (wide) {
         launch_wide_select(*wp.d, *wp.io, a.g, wp.B, wp.slice, sa.blocks_per_head, st);
-        return 3;
+        return 3 + plan_after_wide();
       }
       a.select_only = 1;
       step_kernel<DT, G><<<heads, STEP_THREADS, lds, st>>>(a);
@@ -123,7 +134,7 @@ static int launch_step_g(StepArgs& a, int grid, int heads, size_t lds_staged, si
   step_kernel<DT, G><<<grid, STEP_THREADS, a.fuse_select ? lds : 0, st>>>(a);
   if (wide) {
     launch_wide_select(*wp.d, *wp.io, a.g, wp.B, wp.slice, a.blocks_per_head, st);
-    return 3;
+    return 3 + plan_after_wide();
   }
   if (select && !a.fuse_select) {
     a.select_only = 1;
@@ -167,8 +178,15 @@ static void fill_step_args(const Dims& d, int roles, const StepIO& io, Geom g, i
     const size_t n = (size_t)(g.n_cand > 0 ? g.n_cand : 1);
     lds_keys = n * sizeof(uint32_t);
     lds_staged = n * (1 + d.G) * sizeof(uint32_t);
-    if (lds_staged + 8192 > (size_t)d.max_lds) lds_staged = lds_keys;   // cannot fit: do not even ask
+    if (io.plan_new_slots) {
+      a.plan_act_ids = io.plan_act_ids; a.plan_act_slots = io.plan_act_slots;
+      a.plan_new_slots = io.plan_new_slots; a.plan_miss = io.plan_miss;
+    }
+    const size_t plan_bytes = io.plan_new_slots ? plan_lds_ints(d.k) * sizeof(int32_t) : 0;
+    if (lds_staged + plan_bytes + 8192 > (size_t)d.max_lds) lds_staged = lds_keys;   // cannot fit: do not even ask
     if (n <= (size_t)regs_candidates(d.G, roomy)) lds_staged = lds_keys;   // few enough to stay in registers
+    lds_staged += plan_bytes;                      // the recall plan's LDS follows the selection's
+    lds_keys += plan_bytes;
   }
 }
 
@@ -228,7 +246,7 @@ struct LayerArgs {
   int attn_block0;     // index of the first attention block
 };
 
-template <int DT, int G>
+template <int DT, int G, bool HOSTPOOL>
 __global__ __launch_bounds__(STEP_THREADS, STEP_THREADS <= 256 ? 2 : 1) void layer_kernel(LayerArgs a) {
   extern __shared__ uint32_t dyn_lds[];
   if ((int)blockIdx.x < a.attn_block0) {
@@ -237,31 +255,40 @@ __global__ __launch_bounds__(STEP_THREADS, STEP_THREADS <= 256 ? 2 : 1) void lay
   }
   const int ab = blockIdx.x - a.attn_block0, heads = a.s.batch * a.s.n_kv;
   const int head = ab % heads, split = ab / heads;
-  attn_block<DT, STEP_WAVES>(a.at, split, head % a.s.n_kv, head / a.s.n_kv, reinterpret_cast<float*>(dyn_lds));
+  attn_block<DT, STEP_WAVES, HOSTPOOL>(a.at, split, head % a.s.n_kv, head / a.s.n_kv, reinterpret_cast<float*>(dyn_lds));
 }
 
 // experiment builds only: 1 = always separate launches, 0 = one launch whenever it fits
 static const bool g_no_layer_kernel = knob("FKV_NO_LAYER_KERNEL", -1) == 1;
 static const bool g_layer_always = knob("FKV_NO_LAYER_KERNEL", -1) == 0;
 
-template <int DT, int G>
-static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
+template <int DT, int G, bool HOSTPOOL>
+static bool launch_layer_gh(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
   static size_t granted = 48 * 1024;      // dynamic LDS beyond the default has to be granted per function
   if (lds > granted) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<DT, G>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<DT, G, HOSTPOOL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
       (void)hipGetLastError();
       return false;
     }
     granted = lds;
   }
-  layer_kernel<DT, G><<<grid, STEP_THREADS, lds, st>>>(a);
+  layer_kernel<DT, G, HOSTPOOL><<<grid, STEP_THREADS, lds, st>>>(a);
   return true;
+}
+template <int DT, int G>
+static bool launch_layer_g(const LayerArgs& a, int grid, size_t lds, hipStream_t st) {
+  return a.at.host_pool ? launch_layer_gh<DT, G, true>(a, grid, lds, st) : launch_layer_gh<DT, G, false>(a, grid, lds, st);
 }
 
 bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, hipStream_t st) {
   const int roles = ROLE_APPEND | ROLE_CORR | ROLE_SELECT;
-  if (g_no_layer_kernel || io.pd.placement != 0 || d.k == 0 || append_races_selection(roles, g)) return false;
+  if (g_no_layer_kernel || d.k == 0 || append_races_selection(roles, g)) return false;
+  if (io.pd.placement != 0) {
+    // KV in a host pool: the selecting blocks make the recall plan, the attention blocks of a corrected head fetch its
+    // missing pages themselves; the tagged words have to hold a page id and a slot
+    if (!io.plan_new_slots || !lio.host_pool || d.max_pages > TAGGED_MAX_PAGES || 2 * d.k > TAGGED_MAX_SLOTS) return false;
+  }
   {   // a candidate list long enough for the selection to be spread over several blocks takes the separate launches
     int wb, ws;
     if (io.bmax && knob("FKV_NO_WIDE_SELECT", 0) == 0 && wide_plan(d, g, &wb, &ws)) return false;
@@ -278,10 +305,13 @@ bool launch_layer(const Dims& d, const StepIO& io, const LayerIO& lio, Geom g, h
     a.s.select_only = 0;
     a.s.tagged = lio.tagged;
     a.s.epoch = lio.epoch;
+    a.s.plan_lds_off = (int)((lds_staged - (a.s.plan_new_slots ? plan_lds_ints(d.k) * sizeof(int32_t) : 0)) / sizeof(uint32_t));
     const int heads = d.batch * d.n_kv;
     const int n_att = g.n_sink + d.k + g.n_win + (g.r > 0 ? 1 : 0);
     AttnArgs& at = a.at;
-    at.pd = io.pd; at.q = io.q; at.act_ids = lio.act_ids; at.new_ids = io.ids; at.act_slots = nullptr; at.new_slots = nullptr;
+    at.pd = io.pd; at.q = io.q; at.act_ids = lio.act_ids; at.new_ids = io.ids;
+    at.act_slots = io.plan_act_slots; at.new_slots = io.plan_new_slots;       // (null with the KV in HBM)
+    at.host_pool = lio.host_pool; at.max_pages = d.max_pages;
     at.flags = io.flags; at.use = 2; at.part_o = lio.part_o; at.part_ml = lio.part_ml; at.max_splits = lio.max_splits;
     at.pps = attn_pages_per_block(n_att, heads, lio.max_splits, STEP_WAVES);
     at.n_splits = (n_att + at.pps - 1) / at.pps;

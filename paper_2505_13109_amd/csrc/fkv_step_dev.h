@@ -23,6 +23,7 @@
 //            lower page id.
 #pragma once
 #include "fkv_device.h"
+#include "fkv_plan_dev.h"
 
 #pragma clang fp contract(off)
 
@@ -77,7 +78,16 @@ struct StepArgs {
   long long* tstamp;         // debug: 100 MHz timestamps of head 0's phases (may be null)
   unsigned long long* tagged; // if not null: [heads][k], every picked id once more as (epoch << 32 | id): a block of
   int epoch;                  // this launch that waits for the selection polls the word it needs
+  // KV in a host pool: the selecting block also makes the head's recall plan (fkv_plan_dev.h).  plan_new_slots null:
+  // not here.  The tagged words then carry, instead of the bare id, what a waiting attention wave needs to fetch the
+  // page: tagged_pick() of (page id, slot, miss).
+  const int32_t* plan_act_ids;
+  const int32_t* plan_act_slots;
+  int32_t* plan_new_slots;
+  int32_t* plan_miss;
+  int plan_lds_off;           // where the plan's LDS starts, in 32-bit words of the block's dynamic LDS
 };
+
 
 // ---------------------------------------------------------------------------------
 // role: append one token (Sec. 3.2 summaries; Sec. 4.2 paged layout).  128 active threads.
@@ -457,13 +467,33 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   // with the step's epoch in one 64-bit word, so that a waiting attention wave sees "this step's id" in one read
   unsigned long long* tag = a.tagged ? a.tagged + (size_t)head * k : nullptr;
   const unsigned long long tag_hi = (unsigned long long)(uint32_t)a.epoch << 32;
+  // With a recall plan to make, the ids are only collected in the plan's LDS here and everything goes out after it.
+  int32_t* plan_sm = reinterpret_cast<int32_t*>(key) + a.plan_lds_off;
+  int32_t* plan_nid = a.plan_new_slots ? plan_sm + 4 * k : nullptr;
   auto put_id = [&](int pos, int id) {
+    if (plan_nid) { plan_nid[pos] = id; return; }
     __hip_atomic_store(out + pos, id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tag) __hip_atomic_store(tag + pos, tag_hi | (uint32_t)id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (outu) outu[pos] = id;
   };
+  auto plan_and_publish = [&]() {
+    if (!plan_nid) return;
+    __syncthreads();                                   // the ids are all in LDS
+    plan_head<STEP_THREADS>(out, a.plan_act_ids + (size_t)head * k, a.plan_act_slots + (size_t)head * k,
+                            a.plan_new_slots + (size_t)head * k, a.plan_miss + (size_t)head * (1 + 3 * k), k, a.g.n_full,
+                            plan_sm, true);
+    const int32_t* nslot = plan_sm + 5 * k;
+    for (int i = tid; i < k; i += STEP_THREADS) {
+      const int id = plan_nid[i], s = nslot[i];
+      __hip_atomic_store(out + i, id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tag) __hip_atomic_store(tag + i, tag_hi | tagged_pick(id, s & (TAGGED_MAX_SLOTS - 1), (s & PLAN_MISS_BIT) != 0),
+                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (outu) outu[i] = id;
+    }
+  };
   if (kk == 0) {
     for (int i = tid; i < k; i += STEP_THREADS) put_id(i, -1);
+    plan_and_publish();
     return;
   }
 #ifdef FKV_SEL_STAMPS
@@ -707,6 +737,7 @@ __device__ __forceinline__ void select_block(const StepArgs& a, int head, uint32
   radix_topk(key, n, kk, hist, s_scan, [&](int pos, int j) { put_id(pos, lo + j); });
   FKV_SEL_MARK(4);
   for (int i = kk + tid; i < k; i += STEP_THREADS) put_id(i, -1);   // padding
+  plan_and_publish();
 #ifdef FKV_SEL_STAMPS
   if (a.tstamp && head == 0 && tid == 0) {
     a.tstamp[40] = sel_t0; a.tstamp[41] = sel_t1; a.tstamp[42] = sel_t2; a.tstamp[43] = sel_t3;

@@ -290,6 +290,8 @@ def test_c3_full_context_one_layer_all_requests():
         pr.step(0, t, deep=(t % 8 == 0))
         if t % 16 == 15:
             print("c3 step", t, pr.stats, flush=True)
+    # this size takes the separate launches: scan, selection with the recall plan, the corrected heads' gather, attention
+    assert pr.g.step_launches(0) == 4
     torch.cuda.synchronize()
     for r in range(wl.batch):
         pr.check_cached_pages(0, r, r, where=2)
@@ -298,12 +300,16 @@ def test_c3_full_context_one_layer_all_requests():
 
 
 def test_c3_shape_host_pool_recall():
-    """Config 3 shape with the KV pool in pinned host memory (scaled: 2 requests, 16K context, 2 layers)."""
+    """Config 3 shape with the KV pool in pinned host memory (scaled: 2 requests, 16K context, 2 layers).  At this size
+    the layer-step is one launch on the compute stream: the selecting blocks make the recall plan and the attention
+    blocks of a corrected head fetch its missing pages from the host pool themselves; the other heads' recall follows
+    on the copy stream."""
     wl = W.get_workload("c3").scaled(batch=2, ctx=16384 - 40, steps=96)
     pr = _pair(wl, [0, 31], steps=96)
     for t in range(96):
         for li in range(2):
             pr.step(li, t)
+            assert pr.g.step_launches(li) == 1
         if t % 24 == 23:
             torch.cuda.synchronize()
             for li in range(2):
@@ -651,6 +657,7 @@ def test_host_pool_fp16_ragged_growth():
     pr = _pair(wl, [4])
     for t in range(wl.steps):
         pr.step(0, t, deep=(t % 5 == 0))
+        assert pr.g.step_launches(0) == 1
         if t % 64 == 63:
             torch.cuda.synchronize()
             pr.check_cached_pages(0, 1, 1, where=1)
