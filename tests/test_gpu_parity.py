@@ -650,6 +650,58 @@ def test_pooling_variants_with_the_host_pool():
     pr.close()
 
 
+def test_host_pool_deferred_recall_shared_by_groups_of_layers():
+    """Eleven layers with the KV in the host pool, one launch per layer-step.  The recall of the uncorrected heads
+    (Sec. 3.2: off the critical path, for the next step) is kept back and submitted for up to eight layers at once, so
+    nothing is read back here until a whole decode step of all layers has been enqueued: first full steps (a group of
+    eight, then the last three with the last layer), then steps over five layers only, where nothing triggers the
+    submission until the same layers step again, then an explicit fkv_flush before the copy stream is synchronised and
+    the page cache inspected."""
+    wl = W.get_workload("c3").scaled(batch=1, ctx=4096 - 9, steps=20)
+    n_lay = 11
+    pr = _pair(wl, list(range(0, 2 * n_lay, 2)), steps=20)
+
+    def whole_step(t, layers):
+        res, outs = {}, {}
+        for li in layers:
+            res[li] = pr.step(li, t, check=False)
+            assert pr.g.step_launches(li) == 1
+            outs[li] = pr.out.clone()                 # (device-side copy on the compute stream: no call into the library)
+        return res, outs
+
+    def compare(t, res, outs):
+        for li in res:
+            got = pr.read_step(li, deep=False)
+            got["out"] = outs[li].cpu().numpy()
+            pr.compare(li, t, res[li], got, False)
+
+    t = 0
+    for _ in range(10):
+        res, outs = whole_step(t, range(n_lay))
+        compare(t, res, outs)
+        t += 1
+    # five layers only, two steps without a read in between: their recalls stay on the list until the same layers step
+    # again (the other six layers rest: each layer's context is its own)
+    from harness import rel_err_per_head, TOL_OUT
+    res_a, outs_a = whole_step(t, range(5))
+    t += 1
+    res_b, outs_b = whole_step(t, range(5))
+    compare(t, res_b, outs_b)
+    t += 1
+    for li in res_a:                                  # of the step before, only the outputs are still around
+        assert rel_err_per_head(outs_a[li].cpu().numpy()[0], res_a[li][0]["out"]).max() <= TOL_OUT
+    res, outs = whole_step(t, range(5))
+    pr.g.flush()
+    pr.copy_stream.synchronize()
+    torch.cuda.current_stream().synchronize()
+    compare(t, res, outs)
+    for li in (0, 4):
+        pr.check_cached_pages(li, 0, 3, where=2)
+    assert pr.stats["misses"] > 0 and 0 < pr.stats["flagged"] < pr.stats["heads"]
+    print("deferred groups", pr.stats)
+    pr.close()
+
+
 def test_host_pool_fp16_ragged_growth():
     """fp16, G = 5, two requests, host pool, context growing from 40 tokens through page fills (offloads),
     the first candidates and the first recalls."""
