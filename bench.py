@@ -36,7 +36,7 @@ MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9428799, "layer_kernel": 14066018}
 TRAFFIC_SOURCE = ("profiles/layer_step_c2_pmc.txt: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE over this command with "
                   "--calibration-copy, KiB per dispatch scaled by what the same counters read for a 256 MiB copy")
 # the same for the two kernels of the batch-32 shape (profiles/decode_step_c2_batch32_kernels_and_pmc.txt)
-MEASURED_TRAFFIC_BYTES_B32 = {"attn_kernel": 273626971, "step_kernel": 137405155}
+MEASURED_TRAFFIC_BYTES_B32 = {"attn_kernel": 273626971, "scan_kernel": 137405155}
 TRAFFIC_SOURCE_B32 = "profiles/decode_step_c2_batch32_kernels_and_pmc.txt (same method, batch-32 shape)"
 
 
@@ -117,9 +117,9 @@ def saturated_rate(torch, fkv, wl, batch, layers=2, steps=16, warmup=4):
              "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": attn_b / attn_s / 1e9 / HBM_PEAK_GBPS,
              "traffic": MEASURED_TRAFFIC_BYTES_B32["attn_kernel"] if batch == 32 and wl.name == "c2" else None,
              "traffic_source": TRAFFIC_SOURCE_B32, "algorithmic_bytes_per_launch": attn_b, "avg_launch_us": attn_s * 1e6},
-            {"bound": "hbm", "kernel": "step_kernel (page-weight scan over the min-max summaries) + the selection launch behind it",
+            {"bound": "hbm", "kernel": "scan_kernel (page-weight scan over the min-max summaries) + the selection launch behind it",
              "achieved": score_b / scan_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": score_b / scan_s / 1e9 / HBM_PEAK_GBPS,
-             "traffic": MEASURED_TRAFFIC_BYTES_B32["step_kernel"] if batch == 32 and wl.name == "c2" else None,
+             "traffic": MEASURED_TRAFFIC_BYTES_B32["scan_kernel"] if batch == 32 and wl.name == "c2" else None,
              "traffic_source": TRAFFIC_SOURCE_B32, "algorithmic_bytes_per_launch": score_b,
              "avg_launch_us": scan_s * 1e6, "launches_per_scan": sel_n // (4 * layers)}]
     return {"roofline": roof, "batch": batch, "layers": layers, "steps": steps, "launches_per_layer_step": launches,
@@ -180,6 +180,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the number of requests (stated in config.workload)")
     ap.add_argument("--tau", type=float, default=None, help="override the correction threshold (stated in config.workload)")
     ap.add_argument("--rho", type=float, default=None, help="override the adjacent-step query correlation (stated in config.workload)")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="placement 1: the deferred recall on the compute stream instead of a copy stream (exposed; for the design notes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--standin-mb", type=int, default=0,
                     help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
@@ -263,7 +265,7 @@ def main():
                "prefill_GBps_read_plus_written": (2 * kv_bytes + kv_bytes // 32) / (prefill_ms / prefill_layers / 1e3) / 1e9}
     out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
-    copy_stream = torch.cuda.Stream()
+    copy_stream = stream if args.one_stream else torch.cuda.Stream()
 
     nhd_attached = None
     if args.nhd_stream and wl.placement == 1:

@@ -156,6 +156,7 @@ struct fkv_ctx {
   // three HIP calls and each stream a few microseconds, so the layers of a decode step share one per kDeferGroup layers.
   std::vector<int> deferred;
   hipStream_t deferred_st = nullptr, deferred_cs = nullptr;
+  std::vector<std::pair<hipEvent_t, hipStream_t>> waited;   // (recall event, stream that already waits for its latest record)
   uint16_t* nhd_pool = nullptr;       // fkv_attach_nhd_pool: recalled pages also land, converted, in this NHD pool
   int32_t* nhd_slot_pages = nullptr;
   int nhd_slots = 0;
@@ -222,13 +223,16 @@ struct fkv_ctx {
 // step finished: it reuses the miss list and flags that recall reads, and the slots it fills.
 static int wait_recall(fkv_ctx* ctx, LayerState& ls, hipStream_t st) {
   if (ls.recall_outstanding) {
-    // Usually that recall ended long ago (it had a whole decode step): then the host sees its event complete, what
-    // it wrote is visible to every later launch, and the stream needs no dependency at all.
-    hipError_t e = hipEventQuery(ls.recall_event);
-    if (e != hipSuccess) {
-      (void)hipGetLastError();                       // "not ready" is not an error here
-      e = hipStreamWaitEvent(st, ls.recall_event, 0);
+    // Layers whose recalls were submitted together share the event: the stream waits for it once, with the first of
+    // them that comes round again (a dependency between streams costs the host and the waiting stream microseconds
+    // even when it is satisfied long since, as it is here: the recall had a whole decode step).
+    bool covered = false;
+    for (const auto& w : ctx->waited)
+      if (w.first == ls.recall_event && w.second == st) covered = true;
+    if (!covered) {
+      hipError_t e = hipStreamWaitEvent(st, ls.recall_event, 0);
       if (e != hipSuccess) return ctx->hip_fail(e, "hipStreamWaitEvent");
+      ctx->waited.emplace_back(ls.recall_event, st);
     }
     ls.recall_outstanding = false;
   }
@@ -321,9 +325,15 @@ static int run_plan(fkv_ctx* ctx, int layer, hipStream_t st) {
   return after_launch(ctx, "plan kernel");
 }
 
+static void forget_waits(fkv_ctx* ctx, hipEvent_t ev) {     // `ev` has just been recorded again
+  auto& w = ctx->waited;
+  for (size_t i = 0; i < w.size();)
+    if (w[i].first == ev) { w[i] = w.back(); w.pop_back(); } else ++i;
+}
+
 // Submit the deferred recalls on the list: one dependency of the copy stream on the compute stream, one gather launch
 // for all listed layers' uncorrected heads, one event that every listed layer's next step looks at.
-constexpr int kDeferGroup = GATHER_MAX_LAYERS;
+constexpr int kDeferGroup = GATHER_MAX_LAYERS;   // (4, 8 and 16 layers per submission measure the same)
 static int flush_deferred(fkv_ctx* ctx) {
   if (ctx->deferred.empty()) return FKV_OK;
   hipStream_t st = ctx->deferred_st, cs = ctx->deferred_cs;
@@ -346,7 +356,10 @@ static int flush_deferred(fkv_ctx* ctx) {
   int rc = after_launch(ctx, "gather kernel");
   if (rc) return rc;
   hipEvent_t done = ctx->layers[ctx->deferred.back()].ev_recall;
-  if (cs != st) FKV_HIP(ctx, hipEventRecord(done, cs));
+  if (cs != st) {
+    FKV_HIP(ctx, hipEventRecord(done, cs));
+    forget_waits(ctx, done);
+  }
   for (int l : ctx->deferred) {
     LayerState& ls = ctx->layers[l];
     ls.recall_unsubmitted = false;
@@ -875,6 +888,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
       rc = fkv_recall_pending(ctx, layer, FKV_HEADS_UNFLAGGED, copy_stream);
       if (rc) return rc;
       FKV_HIP(ctx, hipEventRecord(ls.ev_recall, cs));
+      forget_waits(ctx, ls.ev_recall);
       ls.recall_event = ls.ev_recall;
       deferred = true;     // the next step of this layer waits for it, not this step's attention
     }
