@@ -126,6 +126,9 @@ int fkv_context_len(const fkv_ctx* ctx, int32_t layer);
  * attention blocks of a corrected head wait for that head's selection, made by other blocks of the
  * same launch; the wait is bounded (about 0.1 s).  A block that gives up makes the failure visible
  * on the data path -- every output row of that KV head's query group is NaN -- and sets a flag.
+ * With the KV in a host pool the waves that gave up also left page-cache slots unfilled: the outputs of
+ * every later step of the layer stay NaN while the flag is up, and after FKV_ETIMEOUT the layer has to
+ * be loaded again (fkv_load_prefix) before its results mean anything.
  * That is not expected to happen; this call synchronises the device, returns FKV_ETIMEOUT if it did
  * and clears the flag.  Blocking. */
 int fkv_health(fkv_ctx* ctx, int32_t layer);

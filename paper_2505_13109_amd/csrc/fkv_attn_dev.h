@@ -368,6 +368,12 @@ __device__ __forceinline__ void attn_block(const AttnArgs& a, int split, int m, 
   // NaN in its sum poisons the block's partial and, through the merge, every output row of the
   // KV head's query group.
   if (timed_out) l_run = __builtin_nanf("");
+  if constexpr (HOSTFUSED) {
+    // With the KV in a host pool the wave that gives up also leaves the page-cache slot it was to fill unfilled, while
+    // the recall plan lists the page as cached: the layer's state cannot be trusted from then on.  Every later step of
+    // the layer therefore stays marked -- NaN outputs -- for as long as the flag is up (fkv_health takes it down).
+    if (__hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) l_run = __builtin_nanf("");
+  }
   if (split == 0) FKV_ASTAMP(17);
   // per-wave totals of l over the 4 row blocks
   l_run += __shfl_xor(l_run, 16, 64);

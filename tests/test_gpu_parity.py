@@ -586,6 +586,43 @@ def test_a_wait_that_runs_out_is_reported():
     g.close()
 
 
+def test_a_wait_that_runs_out_with_the_host_pool_marks_the_layer():
+    """The same with the KV in the host pool, where the waves that give up also leave page-cache slots unfilled:
+    the step's outputs are NaN, the next step's too (the layer stays marked while the flag is up), fkv_health reports
+    it once, and after a reload of the layer it decodes normally."""
+    import paper_2505_13109_amd as fkv
+    from harness import to_dev
+    g = fkv.FreeKV(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, max_ctx=4096, budget=512, sink=64,
+                   window=64, tau=1.5, dtype="bf16", placement=1)
+    rng = np.random.default_rng(4)
+    kv = to_dev(W.encode(rng.standard_normal((1, 3000, 2, 128)).astype(np.float32), "bf16"), "bf16")
+    g.load_prefix(0, kv, kv)
+    q = to_dev(W.encode(rng.standard_normal((1, 8, 128)).astype(np.float32), "bf16"), "bf16")
+    kn = to_dev(W.encode(rng.standard_normal((1, 2, 128)).astype(np.float32), "bf16"), "bf16")
+    out = torch.zeros((1, 8, 128), dtype=torch.float32, device="cuda")
+    cs = torch.cuda.Stream()
+    g.decode_step(0, q, kn, kn, out, copy_stream=cs)
+    g.health(0)
+    assert g.step_launches(0) == 1 and torch.isfinite(out).all()
+    g.test_lose_selection(True)
+    g.decode_step(0, q, kn, kn, out, copy_stream=cs)
+    g.test_lose_selection(False)
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all()
+    out.zero_()
+    g.decode_step(0, q, kn, kn, out, copy_stream=cs)   # no wait is lost here, but the flag is still up
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all()
+    with pytest.raises(fkv.FreeKVError, match="gave up waiting"):
+        g.health(0)
+    g.health(0)
+    g.load_prefix(0, kv, kv)
+    g.decode_step(0, q, kn, kn, out, copy_stream=cs)
+    g.health(0)
+    assert torch.isfinite(out).all()
+    g.close()
+
+
 def test_longest_supported_context():
     """max_ctx at its limit (491520 tokens, 15360 pages; G = 8): one more page is refused at creation, and
     a selection and a whole decode step over 15.3K candidate pages match the oracle."""
