@@ -32,11 +32,11 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the split attention kernel at this workload, from
 # `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs scaled by a copy kernel of known
 # size (profiles/layer_step_c2_pmc.txt).  None until measured.
-MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9428799, "layer_kernel": 14066018}
+MEASURED_TRAFFIC_BYTES = {"attn_kernel": 9419082, "layer_kernel": 14076847}
 TRAFFIC_SOURCE = ("profiles/layer_step_c2_pmc.txt: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE over this command with "
                   "--calibration-copy, KiB per dispatch scaled by what the same counters read for a 256 MiB copy")
 # the same for the two kernels of the batch-32 shape (profiles/decode_step_c2_batch32_kernels_and_pmc.txt)
-MEASURED_TRAFFIC_BYTES_B32 = {"attn_kernel": 273626971, "scan_kernel": 137405155}
+MEASURED_TRAFFIC_BYTES_B32 = {"attn_kernel": 273615139, "scan_kernel": 138655032}
 TRAFFIC_SOURCE_B32 = "profiles/decode_step_c2_batch32_kernels_and_pmc.txt (same method, batch-32 shape)"
 
 
