@@ -13,7 +13,9 @@ Prints one JSON line: `value` = layer-steps/s of the whole job; `roofline` = the
 algorithmic HBM bytes per launch over its average launch duration (HIP events on the launch stream)
 against the 8 TB/s peak, with the counter-measured traffic; `cpu_baseline` = the CPU oracle timed on
 one layer of the same workload; `config.saturated_shape` = the same shape with 32 requests, where the
-path is bound by bandwidth rather than by its chain of dependent memory round trips.
+path is bound by bandwidth rather than by its chain of dependent memory round trips;
+`config.host_pool_shape` = the same shape (16 layers of it) with the KV pool in pinned host memory, where the
+loop runs at the rate of the host link.
 """
 from __future__ import annotations
 
@@ -128,6 +130,62 @@ def saturated_rate(torch, fkv, wl, batch, layers=2, steps=16, warmup=4):
             "path_frac_of_hbm_peak": (score_b + attn_b) / us / 1e3 / HBM_PEAK_GBPS,
             "attn_kernel_GBps": attn_b / (attn_ms / attn_n * 1e-3) / 1e9,
             "attn_kernel_frac_of_hbm_peak": attn_b / (attn_ms / attn_n * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
+def host_pool_rate(torch, fkv, wl, layers=16, steps=32, warmup=8):
+    """The same shape with the whole KV pool in pinned host memory (a few layers of it): recall of the picked pages
+    that the GPU page cache does not hold, corrected heads inside their attention, the others deferred on a copy
+    stream (Sec. 3.2, 3.3, 4.1).  Reports the loop's rate next to the host link's own."""
+    from paper_2505_13109_amd import binding as B
+    ws = wl.scaled(placement=1, n_layers=layers)
+    dev = torch.device("cuda:0")
+    p = ws.page_size
+    n_probe = 8
+    n_steps = steps + warmup + n_probe
+    ctx = fkv.FreeKV(n_layers=layers, batch=ws.batch, n_q_heads=ws.n_q_heads, n_kv_heads=ws.n_kv_heads,
+                     max_ctx=((ws.ctx + n_steps + 16 + p - 1) // p) * p, budget=ws.budget, sink=ws.sink,
+                     window=ws.window, tau=ws.tau, dtype=ws.dtype, placement=1)
+    kv, q, k_new, v_new = gen_inputs(torch, ws, n_steps, dev)
+    for layer in range(layers):
+        ctx.load_prefix(layer, kv((ws.batch, ws.ctx, ws.n_kv_heads, ws.head_dim)), kv((ws.batch, ws.ctx, ws.n_kv_heads, ws.head_dim)))
+    out = torch.empty((layers, ws.batch, ws.n_q_heads, ws.head_dim), dtype=torch.float32, device=dev)
+    stream, copy_stream = torch.cuda.current_stream(), torch.cuda.Stream()
+
+    def run(t0, t1):
+        for t in range(t0, t1):
+            for layer in range(layers):
+                ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer], stream=stream, copy_stream=copy_stream)
+
+    run(0, warmup)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    run(warmup, warmup + steps)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t_begin) / (steps * layers) * 1e6
+    launches = ctx.step_launches(0)
+    miss = picked = 0
+    for t in range(warmup + steps, n_steps):          # page-cache misses of a few more (untimed) steps
+        for layer in range(layers):
+            ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer], stream=stream, copy_stream=copy_stream)
+            miss += int(ctx.debug_read(layer, B.DBG_MISS)[..., 0].sum())
+            picked += ws.batch * ws.n_kv_heads * ws.k_pages
+    for layer in range(layers):
+        ctx.health(layer)
+    ctx.close()
+    src = torch.empty(1 << 29, dtype=torch.uint8, pin_memory=True)      # the host link's own rate: a plain pinned copy
+    dst = torch.empty(1 << 29, dtype=torch.uint8, device=dev)
+    dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    dst.copy_(src, non_blocking=True)
+    c1.record()
+    torch.cuda.synchronize()
+    link = (1 << 29) / (c0.elapsed_time(c1) / 1e3) / 1e9
+    recalled = miss / max(n_probe * layers, 1) * 16384
+    return {"layers": layers, "steps": steps, "launches_per_layer_step_on_the_compute_stream": launches,
+            "us_per_layer_step": us, "page_miss_rate": miss / max(picked, 1), "recall_bytes_per_layer_step": recalled,
+            "recall_GBps_over_the_whole_step": recalled / us / 1e3, "pinned_copy_GBps": link}
 
 
 def _oracle_worker(job):
@@ -475,6 +533,10 @@ def main():
             res["config"]["saturated_shape"] = sat
         except Exception as e:           # noqa: BLE001
             res["config"]["saturated_shape"] = {"error": f"{type(e).__name__}: {e}"}
+        try:                             # and the same shape with the KV pool in pinned host memory
+            res["config"]["host_pool_shape"] = host_pool_rate(torch, fkv, wl)
+        except Exception as e:           # noqa: BLE001
+            res["config"]["host_pool_shape"] = {"error": f"{type(e).__name__}: {e}"}
     if cpu is not None:
         res["cpu_baseline"] = cpu
     print(json.dumps(res))

@@ -266,9 +266,10 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer);
  * ones) -> deferred recall for the other heads on copy_stream -> commit.
  * No host synchronisation.  copy_stream may equal compute_stream.
  * When the layer-step runs as one launch with the KV in a host pool, the deferred recall is not
- * put on copy_stream at once: up to 8 layers' recalls are submitted together (one dependency
- * between the two streams instead of one per layer) -- with the 8th such layer, with the last
- * layer of the context, with the same layer's next step, and by any other call on the context.
+ * put on copy_stream at once: the recalls of a quarter of the context's layers (at most 8) are
+ * submitted together (one dependency between the two streams instead of one per layer) -- with
+ * the last layer of such a group, with the last layer of the context, with the same layer's
+ * next step, and by any other call on the context.
  * A caller that wants them on copy_stream now (to synchronise that stream itself) calls fkv_flush. */
 int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* k_new_dev,
                     const void* v_new_dev, float* out_dev, void* compute_stream, void* copy_stream);

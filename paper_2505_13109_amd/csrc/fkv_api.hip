@@ -153,8 +153,11 @@ struct fkv_ctx {
   int device = 0;                     // the HIP device the context was created on
   hipEvent_t ev_fork = nullptr;
   // Deferred recalls of one-launch layer-steps that are not submitted yet: a cross-stream dependency costs the host
-  // three HIP calls and each stream a few microseconds, so the layers of a decode step share one per kDeferGroup layers.
+  // three HIP calls and each stream a few microseconds, so several layers of a decode step share one.
   std::vector<int> deferred;
+  int defer_group = 1;                // layers per submission: a quarter of the layers, so that a recall submitted with the
+                                      // group's last layer still has three quarters of a decode step before it is needed;
+                                      // at most GATHER_MAX_LAYERS (4, 8 and 16 measure the same on a 32-layer stack)
   hipStream_t deferred_st = nullptr, deferred_cs = nullptr;
   std::vector<std::pair<hipEvent_t, hipStream_t>> waited;   // (recall event, stream that already waits for its latest record)
   uint16_t* nhd_pool = nullptr;       // fkv_attach_nhd_pool: recalled pages also land, converted, in this NHD pool
@@ -333,7 +336,6 @@ static void forget_waits(fkv_ctx* ctx, hipEvent_t ev) {     // `ev` has just bee
 
 // Submit the deferred recalls on the list: one dependency of the copy stream on the compute stream, one gather launch
 // for all listed layers' uncorrected heads, one event that every listed layer's next step looks at.
-constexpr int kDeferGroup = GATHER_MAX_LAYERS;   // (4, 8 and 16 layers per submission measure the same)
 static int flush_deferred(fkv_ctx* ctx) {
   if (ctx->deferred.empty()) return FKV_OK;
   hipStream_t st = ctx->deferred_st, cs = ctx->deferred_cs;
@@ -433,6 +435,7 @@ int fkv_create(const fkv_config* cfg, void* dev_arena, size_t dev_bytes, void* h
   ctx->dev = static_cast<char*>(dev_arena);
   ctx->host = cfg->placement == FKV_PLACE_HOST ? static_cast<char*>(host_arena) : nullptr;
   ctx->layers.resize(cfg->n_layers);
+  ctx->defer_group = cfg->n_layers / 4 < 1 ? 1 : cfg->n_layers / 4 > GATHER_MAX_LAYERS ? GATHER_MAX_LAYERS : cfg->n_layers / 4;
   hipError_t e = hipMemset(dev_arena, 0, l.total);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   const unsigned ev_flags = hipEventDisableTiming;
@@ -859,7 +862,7 @@ int fkv_decode_step(fkv_ctx* ctx, int32_t layer, const void* q_dev, const void* 
       ctx->deferred.push_back(layer);
       ctx->deferred_st = st;
       ctx->deferred_cs = cs;
-      if ((int)ctx->deferred.size() >= kDeferGroup || layer == ctx->cfg.n_layers - 1) {
+      if ((int)ctx->deferred.size() >= ctx->defer_group || layer == ctx->cfg.n_layers - 1) {
         rc = flush_deferred(ctx);
         if (rc) return rc;
       }

@@ -689,11 +689,11 @@ def test_pooling_variants_with_the_host_pool():
 
 def test_host_pool_deferred_recall_shared_by_groups_of_layers():
     """Eleven layers with the KV in the host pool, one launch per layer-step.  The recall of the uncorrected heads
-    (Sec. 3.2: off the critical path, for the next step) is kept back and submitted for up to eight layers at once, so
-    nothing is read back here until a whole decode step of all layers has been enqueued: first full steps (a group of
-    eight, then the last three with the last layer), then steps over five layers only, where nothing triggers the
-    submission until the same layers step again, then an explicit fkv_flush before the copy stream is synchronised and
-    the page cache inspected."""
+    (Sec. 3.2: off the critical path, for the next step) is kept back and submitted for several layers at once (a
+    quarter of the layers: here two), so nothing is read back here until a whole decode step of all layers has been
+    enqueued: first full steps (groups of two, the eleventh layer alone as the context's last), then steps over five
+    layers only, where the fifth layer's recall stays on the list until the same layers step again, then an explicit
+    fkv_flush before the copy stream is synchronised and the page cache inspected."""
     wl = W.get_workload("c3").scaled(batch=1, ctx=4096 - 9, steps=20)
     n_lay = 11
     pr = _pair(wl, list(range(0, 2 * n_lay, 2)), steps=20)
@@ -717,8 +717,8 @@ def test_host_pool_deferred_recall_shared_by_groups_of_layers():
         res, outs = whole_step(t, range(n_lay))
         compare(t, res, outs)
         t += 1
-    # five layers only, two steps without a read in between: their recalls stay on the list until the same layers step
-    # again (the other six layers rest: each layer's context is its own)
+    # five layers only, two steps without a read in between: the fifth layer's recall stays on the list until the same
+    # layers step again (the other six layers rest: each layer's context is its own)
     from harness import rel_err_per_head, TOL_OUT
     res_a, outs_a = whole_step(t, range(5))
     t += 1
