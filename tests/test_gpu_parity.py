@@ -51,6 +51,25 @@ def test_growing_context_ragged_geometry(dtype):
     pr.close()
 
 
+@pytest.mark.parametrize("placement", [0, 1])
+def test_decoding_from_an_empty_context(placement):
+    """Nothing loaded: the first decode step appends token 0 and attends over that one token; the context then grows
+    through the open page, the first full pages, sink and window, the first page offloads (host pool) and the first
+    candidates."""
+    wl = W.Workload("empty", 1, 2, 6, 2, "bf16", 0, 192, 32, 64, 0.75, 200, 0.75, 0.66, 13, placement=placement)
+    pr = _pair(wl, [1])
+    for t in range(wl.steps):
+        pr.step(0, t)
+        if t in (0, 31, 32, 100, 199):
+            pr.check_summaries(0)
+    assert pr.stats["flagged"] > 0
+    if placement == 1:
+        torch.cuda.synchronize()
+        pr.check_cached_pages(0, 1, 0, where=1)
+    print("empty", placement, pr.stats)
+    pr.close()
+
+
 def test_budget_covering_context_is_dense_attention():
     wl = W.Workload("dense", 1, 1, 8, 2, "bf16", 700, 1024, 64, 64, 1.5, 40, 0.9, 0.436, 5)   # tau > 1: every step selects afresh
     pr = _pair(wl, [0])
