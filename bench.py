@@ -15,7 +15,7 @@ against the 8 TB/s peak, with the counter-measured traffic; `cpu_baseline` = the
 one layer of the same workload; `config.saturated_shape` = the same shape with 32 requests, where the
 path is bound by bandwidth rather than by its chain of dependent memory round trips;
 `config.host_pool_shape` = the same shape (16 layers of it) with the KV pool in pinned host memory, where the
-loop runs at the rate of the host link.
+loop runs at the rate of the host link; `config.other_workloads` = the other workload shapes, briefly.
 """
 from __future__ import annotations
 
@@ -186,6 +186,42 @@ def host_pool_rate(torch, fkv, wl, layers=16, steps=32, warmup=8):
     return {"layers": layers, "steps": steps, "launches_per_layer_step_on_the_compute_stream": launches,
             "us_per_layer_step": us, "page_miss_rate": miss / max(picked, 1), "recall_bytes_per_layer_step": recalled,
             "recall_GBps_over_the_whole_step": recalled / us / 1e3, "pinned_copy_GBps": link}
+
+
+def side_rate(torch, fkv, wl, steps, warmup):
+    """Microseconds per layer-step of another workload shape, measured the same way (for the record beside the headline)."""
+    dev = torch.device("cuda:0")
+    p = wl.page_size
+    n_steps = steps + warmup
+    ctx = fkv.FreeKV(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                     max_ctx=((wl.ctx + n_steps + 16 + p - 1) // p) * p, budget=wl.budget, sink=wl.sink,
+                     window=wl.window, tau=wl.tau, dtype=wl.dtype, placement=0)
+    kv, q, k_new, v_new = gen_inputs(torch, wl, n_steps, dev)
+    for layer in range(wl.n_layers):
+        ctx.load_prefix(layer, kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim)), kv((wl.batch, wl.ctx, wl.n_kv_heads, wl.head_dim)))
+    out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def run(t0, t1):
+        for t in range(t0, t1):
+            for layer in range(wl.n_layers):
+                ctx.decode_step(layer, q[t, layer], k_new[t, layer], v_new[t, layer], out[layer], stream=stream)
+
+    run(0, warmup)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    run(warmup, n_steps)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t_begin) / (steps * wl.n_layers) * 1e6
+    launches = ctx.step_launches(0)
+    for layer in range(wl.n_layers):
+        ctx.health(layer)
+    ctx.close()
+    score_b, attn_b = algorithmic_bytes(wl)
+    return {"workload": f"{wl.name}: {wl.n_layers} layers, {wl.n_q_heads}q/{wl.n_kv_heads}kv heads, {wl.dtype}, batch {wl.batch}, "
+                        f"ctx {wl.ctx}, budget {wl.budget}, tau {wl.tau}, rho {wl.rho}, KV in HBM",
+            "steps": steps, "launches_per_layer_step": launches, "us_per_layer_step": us,
+            "path_algorithmic_GBps": (score_b + attn_b) / us / 1e3}
 
 
 def _oracle_worker(job):
@@ -537,6 +573,16 @@ def main():
             res["config"]["host_pool_shape"] = host_pool_rate(torch, fkv, wl)
         except Exception as e:           # noqa: BLE001
             res["config"]["host_pool_shape"] = {"error": f"{type(e).__name__}: {e}"}
+        try:                             # the other workload shapes, briefly (a few layers of the big ones)
+            import workloads as W
+            res["config"]["other_workloads"] = [
+                side_rate(torch, fkv, W.get_workload("c1"), 64, 8),
+                side_rate(torch, fkv, W.get_workload("c4").scaled(n_layers=8), 32, 8),
+                side_rate(torch, fkv, W.get_workload("c5"), 128, 16),
+                side_rate(torch, fkv, W.get_workload("c5").scaled(tau=0.65), 128, 16),
+                side_rate(torch, fkv, W.get_workload("c3").scaled(placement=0, n_layers=4), 16, 4)]
+        except Exception as e:           # noqa: BLE001
+            res["config"]["other_workloads"] = {"error": f"{type(e).__name__}: {e}"}
     if cpu is not None:
         res["cpu_baseline"] = cpu
     print(json.dumps(res))
