@@ -224,6 +224,49 @@ def side_rate(torch, fkv, wl, steps, warmup):
             "path_algorithmic_GBps": (score_b + attn_b) / us / 1e3}
 
 
+def handover_probe(pairs=4000):
+    """What a dependency between two streams costs on this machine: pairs of tiny kernels (an in-place add on 4096 floats),
+    (a) back to back on one stream, (b) the first on stream A, the second on stream B behind an event, A behind an event
+    of B again.  Prints one JSON line; a side measurement for the design notes, not a benchmark of the path."""
+    import torch
+    dev = torch.device("cuda:0")
+    x, y = torch.zeros(4096, device=dev), torch.zeros(4096, device=dev)
+    a, b = torch.cuda.current_stream(), torch.cuda.Stream()
+    ev = [(torch.cuda.Event(), torch.cuda.Event()) for _ in range(64)]
+
+    def one_stream(n):
+        for _ in range(n):
+            x.add_(1.0)
+            y.add_(1.0)
+
+    def two_streams(n):
+        for i in range(n):
+            e, e2 = ev[i % 64]
+            x.add_(1.0)
+            e.record(a)
+            b.wait_event(e)
+            with torch.cuda.stream(b):
+                y.add_(1.0)
+            e2.record(b)
+            a.wait_event(e2)
+
+    def timed(fn):
+        fn(100)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn(pairs)
+        t1 = time.perf_counter()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / pairs * 1e6, (t1 - t0) / pairs * 1e6
+
+    one, one_host = timed(one_stream)
+    two, two_host = timed(two_streams)
+    print(json.dumps({"probe": "stream hand-over", "pairs": pairs,
+                      "us_per_pair_on_one_stream": one, "host_submit_us_per_pair_on_one_stream": one_host,
+                      "us_per_pair_with_two_event_handovers": two, "host_submit_us_per_pair_with_two_event_handovers": two_host,
+                      "us_per_cross_stream_dependency": (two - one) / 2}))
+
+
 def _oracle_worker(job):
     """One layer of the workload through the oracle, one thread: (steps timed, seconds)."""
     wl, layer, budget_s = job
@@ -276,6 +319,8 @@ def main():
     ap.add_argument("--rho", type=float, default=None, help="override the adjacent-step query correlation (stated in config.workload)")
     ap.add_argument("--one-stream", action="store_true",
                     help="placement 1: the deferred recall on the compute stream instead of a copy stream (exposed; for the design notes)")
+    ap.add_argument("--handover-probe", action="store_true",
+                    help="measure what a dependency between two streams costs (empty kernels of the layer kernel's shape) and exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--standin-mb", type=int, default=0,
                     help="per layer-step, also stream this many MB through a plain reduction on the compute stream: "
@@ -299,6 +344,9 @@ def main():
         print("bench.py: this build measures one GPU only (the path shards over KV heads / requests "
               "with no exchange between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.handover_probe:
+        handover_probe()
+        return
 
     import workloads as W
 
