@@ -265,6 +265,10 @@ int fkv_commit(fkv_ctx* ctx, int32_t layer);
  * heads -> attention (corrected heads on the new pages, others on the reused
  * ones) -> deferred recall for the other heads on copy_stream -> commit.
  * No host synchronisation.  copy_stream may equal compute_stream.
+ * Small shapes run all of it as one kernel launch (fkv_step_launches); with the KV in a host pool the
+ * recall of a corrected head then happens inside its attention -- the wave that attends over a page
+ * the cache does not hold reads it from the host pool and puts it into its page-cache slot -- which
+ * leaves the same state: by the end of the step the page is cached and was attended over.
  * When the layer-step runs as one launch with the KV in a host pool, the deferred recall is not
  * put on copy_stream at once: the recalls of a quarter of the context's layers (at most 8) are
  * submitted together (one dependency between the two streams instead of one per layer) -- with
